@@ -1,0 +1,119 @@
+/*
+ * flashprefill.h - C ABI of the MI355X (gfx950) FlashPrefill prefill-attention library.
+ *
+ * One causal GQA attention layer, computed as the paper's three stages
+ * (Appendix B, "Detailed Implementation"):
+ *   (i)   fp_block_search    pattern discovery          Sec. 3.1-3.2, Eq. 1-4, Alg. 1
+ *   (ii)  fp_threshold       max-based dynamic threshold + index compression
+ *                                                        Sec. 3.4, Alg. 2, Appendix A
+ *   (iii) fp_sparse_prefill  index-driven block-sparse attention   Sec. 3.5, Alg. 3
+ *         fp_dense_prefill   full causal attention, the comparison the paper's
+ *                            speedups are quoted against (Experiments, "Baselines")
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library never
+ *     frees or reallocates it.  `cu_seqlens` inside fp_shape is a HOST pointer, read only
+ *     during fp_layout / fp_plan_create.
+ *   - Q and O are [T, Hq, d], K and V are [T, Hkv, d], bf16, contiguous, token-major;
+ *     T = cu_seqlens[nseq].  Sequence s owns tokens cu_seqlens[s] .. cu_seqlens[s+1]-1.
+ *     Query head h reads KV head h / (Hq / Hkv).
+ *   - Blocks of `block` (=128) tokens are aligned to the start of each sequence; a sequence
+ *     of length L has ceil(L / block) blocks, the last one possibly partial.  Query-block
+ *     row r = row_offset[s] + I addresses q-block I of sequence s; m_total = total rows,
+ *     n_max = most blocks in any one sequence.
+ *   - scores: fp32 [Hq, m_total, n_max]; idx: int32 [Hq, m_total, n_max]; cnt: int32
+ *     [Hq, m_total]; lse: fp32 [Hq, T].  Head-major so that one row is contiguous (the
+ *     paper's Alg. 2 indexes [batch, q-block, k-block, head]).
+ *   - Compute calls only enqueue kernels on `hip_stream` (a hipStream_t, NULL = default
+ *     stream): they do not allocate, synchronise or touch host memory.  Calls on one plan
+ *     must be stream-ordered with respect to each other (they share the plan's workspace).
+ *   - Errors are return codes.  Argument checks happen on the host before any launch.
+ *     A launch failure is reported as FP_ERR_DEVICE.  NaN/Inf inputs are not checked.
+ */
+#ifndef FLASHPREFILL_H
+#define FLASHPREFILL_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    FP_OK = 0,
+    FP_ERR_INVALID_ARG = 1, /* null pointer, inconsistent shape, bad cu_seqlens            */
+    FP_ERR_UNSUPPORTED = 2, /* head_dim != 128, block != 128, or more than 4096 blocks/seq  */
+    FP_ERR_DEVICE = 3,      /* HIP runtime error (no device, allocation or launch failure) */
+    FP_ERR_NOMEM = 4        /* host allocation failed                                      */
+} fp_status;
+
+typedef struct {
+    int32_t nseq;              /* sequences in the packed batch, >= 1                         */
+    const int32_t *cu_seqlens; /* HOST, nseq+1 entries, [0] = 0, strictly increasing          */
+    int32_t hq, hkv;           /* query heads, KV heads; hq % hkv == 0                        */
+    int32_t head_dim;          /* 128                                                         */
+    int32_t block;             /* 128 (Appendix A: uniform block size)                        */
+    float scale;               /* softmax scale tau; <= 0 selects 1/sqrt(head_dim)            */
+} fp_shape;
+
+typedef struct {
+    float alpha;           /* threshold factor (Appendix A: 0.12 / 0.18 / 0.08 per model); <= 0 keeps all */
+    int32_t sink_tokens;   /* attention-sink size in tokens (Appendix A: 256); rounded up to blocks      */
+    int32_t window_tokens; /* local-window size in tokens (Appendix A: 512); rounded up to blocks,       */
+                           /* the window includes the diagonal block                                     */
+} fp_params;
+
+typedef struct fp_plan fp_plan; /* opaque: shape tables on the device + workspace (pooled keys) */
+
+const char *fp_status_string(fp_status s);
+
+/* Host only.  Validates `shape` and reports the row bookkeeping.  Any output pointer may be
+ * NULL; row_offset receives nseq+1 entries.  No GPU is touched. */
+fp_status fp_layout(const fp_shape *shape, int32_t *m_total, int32_t *n_max, int32_t *row_offset);
+
+/* Validates `shape`, selects `device`, allocates and fills the plan's device tables and its
+ * workspace (pooled keys: 2 x m_total x Hkv x 128 bf16).  Synchronous.  The plan is immutable
+ * afterwards and may be used for any number of calls; destroy it with fp_plan_destroy after
+ * the work enqueued with it has finished. */
+fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **plan);
+void fp_plan_destroy(fp_plan *plan);
+
+/*
+ * Stage (i).  Alg. 1: mean-pool each key block (stage 1), for every causal block pair
+ * (I, J <= I) reduce the query tile's logits against the pooled key to a max m_IJ and a sum
+ * of exponentials S_IJ (stage 2, Eq. 1-2), bring each row to its max and normalise (stage 3,
+ * Eq. 3-4):  scores[h, r, J] = S'_IJ / (sum_K S'_IK + eps) for J <= I, and 0 for I < J < n_max.
+ * The pair-level causal restriction J <= I is the only mask; a partial last block averages its
+ * valid keys and leaves out missing queries.
+ */
+fp_status fp_block_search(fp_plan *plan, const void *Q, const void *K, float eps, float *scores, void *hip_stream);
+
+/*
+ * Stage (ii).  Alg. 2: per (head, q-block row): thresh = alpha * max_{J<=I} scores (Sec. 3.4),
+ * keep J iff (scores >= thresh or J < sink blocks or 0 <= I-J < window blocks) and J <= I;
+ * idx[h, r, 0..cnt[h, r]) holds the kept J in ascending order.  Entries of idx past cnt are
+ * not written (the paper pads them with the block count and sorts; the compaction here yields
+ * the same prefix without a sort).  `scores` entries with J > I are never read.
+ */
+fp_status fp_threshold(fp_plan *plan, const float *scores, const fp_params *params, int32_t *idx, int32_t *cnt,
+                       void *hip_stream);
+
+/*
+ * Stage (iii).  Alg. 3: for each (head, q-block row) visit only the listed key blocks, online
+ * softmax in base 2, causal mask on the diagonal block only; O = acc / l, lse = m + log2 l
+ * (base-2 log-sum-exp of tau*log2(e)*q.k over the visited, non-future keys).  `lse` may be
+ * NULL.  Lists must be ascending and causal (as fp_threshold emits them); out-of-range entries
+ * are clamped into [0, I] rather than dereferenced.  A row with cnt == 0 yields O = 0.
+ */
+fp_status fp_sparse_prefill(fp_plan *plan, const void *Q, const void *K, const void *V, const int32_t *idx,
+                            const int32_t *cnt, void *O, float *lse, void *hip_stream);
+
+/* Full causal attention with the same kernel family (every block J <= I visited). */
+fp_status fp_dense_prefill(fp_plan *plan, const void *Q, const void *K, const void *V, void *O, float *lse,
+                           void *hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLASHPREFILL_H */

@@ -1,0 +1,229 @@
+// Host side of the C ABI declared in include/flashprefill.h: shape validation, the plan
+// (device tables + workspace) and the kernel launches.  gfx950 only.
+#include "../../include/flashprefill.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <new>
+#include <numeric>
+#include <vector>
+
+#include "fp_attn.hpp"
+#include "fp_device.hpp"
+#include "fp_search.hpp"
+
+namespace {
+
+constexpr int kMaxBlocksPerSeq = 4096;   // (m, S) of one row must fit the score kernel's LDS
+
+struct Layout {
+    int m_total = 0, n_max = 0;
+    std::vector<int32_t> row_offset;
+};
+
+fp_status check_shape(const fp_shape *s, Layout *out) {
+    if (s == nullptr || s->cu_seqlens == nullptr) return FP_ERR_INVALID_ARG;
+    if (s->nseq < 1 || s->hq < 1 || s->hkv < 1 || s->hq % s->hkv != 0) return FP_ERR_INVALID_ARG;
+    if (s->cu_seqlens[0] != 0) return FP_ERR_INVALID_ARG;
+    for (int i = 0; i < s->nseq; ++i)
+        if (s->cu_seqlens[i + 1] <= s->cu_seqlens[i]) return FP_ERR_INVALID_ARG;
+    if (!(s->scale == s->scale) || std::isinf(s->scale)) return FP_ERR_INVALID_ARG;
+    if (s->head_dim != fp::kHeadDim || s->block != fp::kBlock) return FP_ERR_UNSUPPORTED;
+    Layout L;
+    L.row_offset.resize((size_t)s->nseq + 1);
+    L.row_offset[0] = 0;
+    for (int i = 0; i < s->nseq; ++i) {
+        const int64_t len = (int64_t)s->cu_seqlens[i + 1] - s->cu_seqlens[i];
+        const int64_t nb = (len + s->block - 1) / s->block;
+        if (nb > kMaxBlocksPerSeq) return FP_ERR_UNSUPPORTED;
+        L.n_max = std::max<int>(L.n_max, (int)nb);
+        L.row_offset[i + 1] = L.row_offset[i] + (int32_t)nb;
+    }
+    L.m_total = L.row_offset[s->nseq];
+    if (out) *out = std::move(L);
+    return FP_OK;
+}
+
+}  // namespace
+
+struct fp_plan {
+    int device = 0;
+    int nseq = 0, hq = 0, hkv = 0, g = 0, T = 0;
+    int m_total = 0, n_max = 0;
+    float c = 0.f;                    // tau * log2(e)
+    fp::BlockRec *d_blk = nullptr;    // [m_total]
+    int32_t *d_order = nullptr;       // [m_total] rows, largest I first
+    uint16_t *d_kb_hi = nullptr;      // [m_total, hkv, 128] bf16
+    uint16_t *d_kb_lo = nullptr;
+    size_t search_lds = 0;
+    int n_pad = 0;
+};
+
+extern "C" {
+
+const char *fp_status_string(fp_status s) {
+    switch (s) {
+        case FP_OK: return "ok";
+        case FP_ERR_INVALID_ARG: return "invalid argument";
+        case FP_ERR_UNSUPPORTED: return "unsupported shape (head_dim and block must be 128, at most 4096 blocks per sequence)";
+        case FP_ERR_DEVICE: return "HIP device error";
+        case FP_ERR_NOMEM: return "out of host memory";
+    }
+    return "unknown status";
+}
+
+fp_status fp_layout(const fp_shape *shape, int32_t *m_total, int32_t *n_max, int32_t *row_offset) {
+    Layout L;
+    const fp_status st = check_shape(shape, &L);
+    if (st != FP_OK) return st;
+    if (m_total) *m_total = L.m_total;
+    if (n_max) *n_max = L.n_max;
+    if (row_offset) std::copy(L.row_offset.begin(), L.row_offset.end(), row_offset);
+    return FP_OK;
+}
+
+void fp_plan_destroy(fp_plan *p) {
+    if (p == nullptr) return;
+    int prev = 0;
+    const bool have_prev = hipGetDevice(&prev) == hipSuccess;
+    if (hipSetDevice(p->device) == hipSuccess) {
+        if (p->d_blk) (void)hipFree(p->d_blk);
+        if (p->d_order) (void)hipFree(p->d_order);
+        if (p->d_kb_hi) (void)hipFree(p->d_kb_hi);
+        if (p->d_kb_lo) (void)hipFree(p->d_kb_lo);
+    }
+    if (have_prev) (void)hipSetDevice(prev);
+    delete p;
+}
+
+fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
+    if (out == nullptr) return FP_ERR_INVALID_ARG;
+    *out = nullptr;
+    Layout L;
+    const fp_status st = check_shape(shape, &L);
+    if (st != FP_OK) return st;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return FP_ERR_DEVICE;
+
+    fp_plan *p = new (std::nothrow) fp_plan();
+    if (p == nullptr) return FP_ERR_NOMEM;
+    p->device = device;
+    p->nseq = shape->nseq;
+    p->hq = shape->hq;
+    p->hkv = shape->hkv;
+    p->g = shape->hq / shape->hkv;
+    p->T = shape->cu_seqlens[shape->nseq];
+    p->m_total = L.m_total;
+    p->n_max = L.n_max;
+    const float tau = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
+    p->c = tau * fp::kLog2e;
+    p->n_pad = (L.n_max + 31) / 32 * 32;
+    p->search_lds = (size_t)fp::kSearchStageBytes + (size_t)4 * p->n_pad * sizeof(float2);
+
+    std::vector<fp::BlockRec> blk((size_t)L.m_total);
+    for (int s = 0; s < shape->nseq; ++s) {
+        const int a = shape->cu_seqlens[s], b = shape->cu_seqlens[s + 1];
+        for (int r = L.row_offset[s]; r < L.row_offset[s + 1]; ++r) {
+            const int I = r - L.row_offset[s];
+            const int t0 = a + I * fp::kBlock;
+            blk[(size_t)r] = make_int4(t0, std::min(fp::kBlock, b - t0), L.row_offset[s], b);
+        }
+    }
+    // Heaviest rows first: a row's work grows with its block index I within its sequence.
+    std::vector<int32_t> order((size_t)L.m_total);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(),
+                     [&](int32_t x, int32_t y) { return x - blk[(size_t)x].z > y - blk[(size_t)y].z; });
+
+    int prev = 0;
+    (void)hipGetDevice(&prev);
+    bool ok = hipSetDevice(device) == hipSuccess;
+    const size_t kb_bytes = (size_t)L.m_total * p->hkv * fp::kHeadDim * sizeof(uint16_t);
+    ok = ok && hipMalloc(&p->d_blk, blk.size() * sizeof(fp::BlockRec)) == hipSuccess;
+    ok = ok && hipMalloc(&p->d_order, order.size() * sizeof(int32_t)) == hipSuccess;
+    ok = ok && hipMalloc(&p->d_kb_hi, kb_bytes) == hipSuccess;
+    ok = ok && hipMalloc(&p->d_kb_lo, kb_bytes) == hipSuccess;
+    ok = ok && hipMemcpy(p->d_blk, blk.data(), blk.size() * sizeof(fp::BlockRec), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(p->d_order, order.data(), order.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
+    (void)hipSetDevice(prev);
+    if (!ok) {
+        (void)hipGetLastError();
+        fp_plan_destroy(p);
+        return FP_ERR_DEVICE;
+    }
+    *out = p;
+    return FP_OK;
+}
+
+static fp_status launch_status() { return hipGetLastError() == hipSuccess ? FP_OK : FP_ERR_DEVICE; }
+
+// Kernels are enqueued on the calling thread's current device, which must be the plan's.
+static bool on_plan_device(const fp_plan *p) {
+    int cur = -1;
+    return hipGetDevice(&cur) == hipSuccess && cur == p->device;
+}
+
+fp_status fp_block_search(fp_plan *p, const void *Q, const void *K, float eps, float *scores, void *hip_stream) {
+    if (p == nullptr || Q == nullptr || K == nullptr || scores == nullptr || !(eps >= 0.f)) return FP_ERR_INVALID_ARG;
+    if (!on_plan_device(p)) return FP_ERR_DEVICE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    fp::pool_k_kernel<<<dim3(p->m_total, p->hkv), 256, 0, st>>>(static_cast<const uint16_t *>(K), p->d_blk, p->hkv,
+                                                                 p->d_kb_hi, p->d_kb_lo);
+    const int nchunk = (p->g + 3) / 4;
+    fp::search_kernel<<<dim3(p->m_total * p->hkv * nchunk), 256, p->search_lds, st>>>(
+        static_cast<const uint16_t *>(Q), p->d_kb_hi, p->d_kb_lo, p->d_blk, p->d_order, p->m_total, p->n_max, p->n_pad,
+        p->hq, p->hkv, p->g, nchunk, p->c, eps, scores);
+    return launch_status();
+}
+
+fp_status fp_threshold(fp_plan *p, const float *scores, const fp_params *params, int32_t *idx, int32_t *cnt,
+                       void *hip_stream) {
+    if (p == nullptr || scores == nullptr || params == nullptr || idx == nullptr || cnt == nullptr)
+        return FP_ERR_INVALID_ARG;
+    if (params->sink_tokens < 0 || params->window_tokens < 0 || !(params->alpha == params->alpha))
+        return FP_ERR_INVALID_ARG;
+    if (!on_plan_device(p)) return FP_ERR_DEVICE;
+    const int sinkB = (params->sink_tokens + fp::kBlock - 1) / fp::kBlock;
+    const int winB = (params->window_tokens + fp::kBlock - 1) / fp::kBlock;
+    const int rows = p->hq * p->m_total;
+    fp::threshold_kernel<<<dim3((rows + 3) / 4), 256, 0, static_cast<hipStream_t>(hip_stream)>>>(
+        scores, p->d_blk, p->m_total, p->n_max, p->hq, params->alpha, sinkB, winB, idx, cnt);
+    return launch_status();
+}
+
+static fp_status launch_attn(fp_plan *p, bool sparse, const void *Q, const void *K, const void *V, const int32_t *idx,
+                             const int32_t *cnt, void *O, float *lse, void *hip_stream) {
+    if (!on_plan_device(p)) return FP_ERR_DEVICE;
+    const int n_super = p->m_total * p->hkv;
+    const int grid = (n_super + 7) / 8 * 8 * p->g;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const uint16_t *q = static_cast<const uint16_t *>(Q), *k = static_cast<const uint16_t *>(K),
+                   *v = static_cast<const uint16_t *>(V);
+    uint16_t *o = static_cast<uint16_t *>(O);
+    if (sparse)
+        fp::attn_kernel<true><<<dim3(grid), 256, 0, st>>>(q, k, v, idx, cnt, p->d_blk, p->d_order, p->m_total, p->n_max,
+                                                           p->hq, p->hkv, p->g, p->T, p->c, o, lse);
+    else
+        fp::attn_kernel<false><<<dim3(grid), 256, 0, st>>>(q, k, v, nullptr, nullptr, p->d_blk, p->d_order, p->m_total,
+                                                            p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
+    return launch_status();
+}
+
+fp_status fp_sparse_prefill(fp_plan *p, const void *Q, const void *K, const void *V, const int32_t *idx,
+                            const int32_t *cnt, void *O, float *lse, void *hip_stream) {
+    if (p == nullptr || Q == nullptr || K == nullptr || V == nullptr || idx == nullptr || cnt == nullptr || O == nullptr)
+        return FP_ERR_INVALID_ARG;
+    return launch_attn(p, true, Q, K, V, idx, cnt, O, lse, hip_stream);
+}
+
+fp_status fp_dense_prefill(fp_plan *p, const void *Q, const void *K, const void *V, void *O, float *lse,
+                           void *hip_stream) {
+    if (p == nullptr || Q == nullptr || K == nullptr || V == nullptr || O == nullptr) return FP_ERR_INVALID_ARG;
+    return launch_attn(p, false, Q, K, V, nullptr, nullptr, O, lse, hip_stream);
+}
+
+}  // extern "C"
