@@ -15,6 +15,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # packed-fp32 instruction selection is switched off for all device code
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # device code only: NaNs are not honoured (infinities still are; the kernels use -inf as the
+    # masked-logit value), which lets max reductions compile to v_max3_f32 without canonicalising
+    "-Xarch_device", "-fno-honor-nans",
     "-Wall", "-Wno-unused-function",
 ]
 

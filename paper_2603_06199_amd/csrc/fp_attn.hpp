@@ -100,19 +100,32 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     // Staging: thread (row = tid/16 + 16i, chunk = tid%16) moves 16 bytes of K and of V.
     u32x4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
     const int st_row = tid >> 4, st_chunk = tid & 15;
-    const size_t st_col = (size_t)hk * kHeadDim + st_chunk * 8;
-    const size_t tok_stride = (size_t)hkv * kHeadDim;
+    // Loads use a wave-uniform base (first token of the tile, KV head) plus a per-thread 32-bit
+    // byte offset, so the address is one scalar pair + one VGPR.  Only a tile that reaches past
+    // the end of its sequence (ragged last block) needs per-row clamping.
+    const uint32_t row_bytes = (uint32_t)hkv * kHeadDim * 2;
+    const uint32_t st_off = (uint32_t)st_row * row_bytes + (uint32_t)st_chunk * 16;
+    const char *Kb = reinterpret_cast<const char *>(K) + (size_t)hk * kHeadDim * 2;
+    const char *Vb = reinterpret_cast<const char *>(V) + (size_t)hk * kHeadDim * 2;
 #define FP_LOAD_ROW(i_, kr_, vr_)                                                                         \
     {                                                                                                     \
-        int tok_ = tok0_ + 16 * (i_);                                                                     \
-        tok_ = tok_ < last_tok ? tok_ : last_tok; /* keys past a ragged end are masked as future keys */  \
-        const size_t off_ = (size_t)tok_ * tok_stride + st_col;                                           \
-        kr_ = *reinterpret_cast<const u32x4 *>(K + off_);                                                 \
-        vr_ = *reinterpret_cast<const u32x4 *>(V + off_);                                                 \
+        uint32_t o_ = st_off + 16u * (i_) * row_bytes;                                                    \
+        if (ragged_) {                                                                                    \
+            int tok_ = tok0_ + st_row + 16 * (i_);                                                        \
+            tok_ = tok_ < last_tok ? tok_ : last_tok; /* keys past the end are masked as future keys */   \
+            o_ = (uint32_t)(tok_ - base_tok_) * row_bytes + (uint32_t)st_chunk * 16; /* tok_ >= base_tok_ */ \
+        }                                                                                                 \
+        kr_ = *reinterpret_cast<const u32x4 *>(kbase_ + o_);                                              \
+        vr_ = *reinterpret_cast<const u32x4 *>(vbase_ + o_);                                              \
     }
 #define FP_LOAD_TILE(t)                                                                                   \
     do {                                                                                                  \
-        const int tok0_ = seq_tok0 + FP_TILE_BLOCK(t) * kBlock + ((t) & 1) * kAttnTileKeys + st_row;      \
+        const int tok0_ = seq_tok0 + FP_TILE_BLOCK(t) * kBlock + ((t) & 1) * kAttnTileKeys;               \
+        const bool ragged_ = tok0_ + kAttnTileKeys - 1 > last_tok;                                        \
+        /* the base never lies past the sequence end, so the unsigned row offsets cannot wrap */          \
+        const int base_tok_ = tok0_ < last_tok ? tok0_ : last_tok;                                        \
+        const char *kbase_ = Kb + (size_t)base_tok_ * row_bytes;                                          \
+        const char *vbase_ = Vb + (size_t)base_tok_ * row_bytes;                                          \
         FP_LOAD_ROW(0, kr0, vr0) FP_LOAD_ROW(1, kr1, vr1) FP_LOAD_ROW(2, kr2, vr2) FP_LOAD_ROW(3, kr3, vr3) \
     } while (0)
 #define FP_STORE_ROW(i_, kr_, vr_)                                                                        \
@@ -133,17 +146,30 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     float m_run = -INFINITY;   // running row max of the raw dot products (before scaling by c)
     float l_run = 0.f;         // this lane's share of the running row sum
 
-    if (ntiles > 0) {
-        FP_LOAD_TILE(0);
-        FP_STORE_TILE(0);
-        if (ntiles > 1) FP_LOAD_TILE(1);
+    const int q_local = 32 * w + (l & 31);
+    if (ntiles == 0) {   // empty list: O = 0, lse = -inf (uniform exit, before any barrier)
+        if (q_local < bi.y) {
+            uint16_t *op = O + ((size_t)(bi.x + q_local) * hq + h) * kHeadDim + 64 * half;
+            const u32x4 z = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4 *>(op + 8 * i) = z;
+            if (lse != nullptr && half == 0) lse[(size_t)h * T + bi.x + q_local] = -INFINITY;
+        }
+        return;
     }
+    FP_LOAD_TILE(0);
+    // Pin the Q fragments here: the loads must have landed before the tile loop, otherwise the
+    // compiler keeps a wait on vector-memory loads inside the loop's MFMA section, which in steady
+    // state would wait for the K/V prefetch issued moments earlier.
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[ks]));
+    FP_STORE_TILE(0);
+    if (ntiles > 1) FP_LOAD_TILE(1);
     __syncthreads();
 
     const int k_frag = (l & 31) * kAttnKStride + half * 16;
     // transpose-read base: row 4*half + (l%16)/4, dims 16*((l%32)/16) + 4*(l%4)
     const int v_frag = 2 * kAttnKTile + (4 * half + ((l & 15) >> 2)) * kAttnVStride + (16 * ((l & 31) >> 4) + 4 * (l & 3)) * 2;
-    const int q_local = 32 * w + (l & 31);
 
     for (int t = 0; t < ntiles; ++t) {
         const int cur = t & 1;
@@ -174,9 +200,13 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
                     if (kk + 32 > lim) s1[i] = -INFINITY;
                 }
             }
-            float tm = fmaxf(s0[0], s1[0]);
+            float ta = max3(s0[0], s0[1], s0[2]), tb = max3(s1[0], s1[1], s1[2]);
 #pragma unroll
-            for (int i = 1; i < 16; ++i) tm = fmaxf(tm, fmaxf(s0[i], s1[i]));
+            for (int i = 3; i < 15; i += 2) {
+                ta = max3(ta, s0[i], s0[i + 1]);
+                tb = max3(tb, s1[i], s1[i + 1]);
+            }
+            float tm = max3(ta, s0[15], max3(tb, s1[15], s1[15]));
             tm = fmaxf(tm, __shfl_xor(tm, 32));
             const float m_new = fmaxf(m_run, tm);
             if (__ballot(m_new > m_run)) {
@@ -189,17 +219,23 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
                 m_run = m_new;
             }
             const float mc = m_run * c;
+            // p = 2^(c*s - c*m), rounded to bf16 for the PV product; the row sum is taken over the
+            // rounded values (the ones that multiply V), two per VALU op.
             bf16x8 pb[2][2];
-            float ps = 0.f;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const float p0 = fast_exp2(__builtin_fmaf(s0[i], c, -mc));
-                const float p1 = fast_exp2(__builtin_fmaf(s1[i], c, -mc));
-                ps += p0 + p1;
-                pb[0][i >> 3][i & 7] = (__bf16)p0;
-                pb[1][i >> 3][i & 7] = (__bf16)p1;
+            for (int i = 0; i < 16; i += 2) {
+                bf16x2 a, b;
+                a[0] = (__bf16)fast_exp2(__builtin_fmaf(s0[i], c, -mc));
+                a[1] = (__bf16)fast_exp2(__builtin_fmaf(s0[i + 1], c, -mc));
+                b[0] = (__bf16)fast_exp2(__builtin_fmaf(s1[i], c, -mc));
+                b[1] = (__bf16)fast_exp2(__builtin_fmaf(s1[i + 1], c, -mc));
+                l_run = add_pair(a, l_run);
+                l_run = add_pair(b, l_run);
+                pb[0][i >> 3][i & 7] = a[0];
+                pb[0][i >> 3][(i & 7) + 1] = a[1];
+                pb[1][i >> 3][i & 7] = b[0];
+                pb[1][i >> 3][(i & 7) + 1] = b[1];
             }
-            l_run += ps;
             const char *vt = smem + cur * kAttnVTile + v_frag;
 #pragma unroll
             for (int kt2 = 0; kt2 < 2; ++kt2)

@@ -47,4 +47,16 @@ __device__ __forceinline__ float wave_sum(float v) {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// max of three.  The device code is compiled with NaNs not honoured (see build.py), so this
+// becomes one v_max3_f32 instead of three canonicalising v_max_f32 plus the max itself.  It must
+// stay a compiler-visible instruction: the wait states the hardware needs between an MFMA and a
+// VALU read of its result are inserted by the compiler, and inline assembly would not get them.
+__device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
+
+// acc + lo(p) + hi(p) for a packed pair of bf16, one VALU op (v_dot2c_f32_bf16).
+__device__ __forceinline__ float add_pair(bf16x2 p, float acc) {
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    return __builtin_amdgcn_fdot2_f32_bf16(p, ones, acc, false);
+}
+
 }  // namespace fp

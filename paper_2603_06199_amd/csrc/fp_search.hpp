@@ -121,6 +121,13 @@ __global__ __launch_bounds__(256, 1) void search_kernel(
     } while (0)
 
     FP_LOAD_TILE(0);
+    // Pin the Q fragments: their loads must have landed before the tile loop, or the compiler
+    // leaves waits on vector-memory loads between the loop's MFMAs (which in steady state would
+    // wait for the pooled-key prefetch issued just before).
+#pragma unroll
+    for (int qt = 0; qt < 4; ++qt)
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qa[qt][ks]));
     FP_STORE_TILE(0);
     if (ntile > 1) FP_LOAD_TILE(1);
     __syncthreads();
@@ -155,11 +162,13 @@ __global__ __launch_bounds__(256, 1) void search_kernel(
                         if (row >= bi.y) acc[qt][i] = -INFINITY;
                     }
             }
-            float mx = -INFINITY;
+            float mx = max3(acc[0][0], acc[1][0], acc[2][0]);
+            mx = max3(mx, acc[3][0], acc[3][0]);
 #pragma unroll
-            for (int qt = 0; qt < 4; ++qt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, acc[qt][i]);
+            for (int i = 1; i < 16; ++i) {
+                mx = max3(mx, acc[0][i], acc[1][i]);
+                mx = max3(mx, acc[2][i], acc[3][i]);
+            }
             mx = fmaxf(mx, __shfl_xor(mx, 32));
             const float mc = mx * c;
             float sum = 0.f;
