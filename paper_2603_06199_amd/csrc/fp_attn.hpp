@@ -39,8 +39,12 @@ __device__ __forceinline__ s16x4 lds_read_tr(const char *p) {
  *   O^T += V^T P^T (16 MFMA): P^T is already in B-operand layout (registers of S^T, packed to
  *         bf16), V^T fragments come from the row-major V tile through LDS transpose reads.
  *
- * K/V tiles are staged global -> registers -> LDS one tile ahead, and the global loads are
- * issued two tiles ahead, with one barrier per tile.
+ * Software pipeline inside the wave: in step t the wave first issues the QK^T MFMAs of tile t+1
+ * and only then runs the softmax of tile t (VALU) and the PV MFMAs of tile t, so the matrix
+ * pipe works on t+1 while the vector ALU exponentiates t.  The S^T registers alternate between
+ * two sets (steps are unrolled in pairs).  K therefore runs one tile ahead of V in LDS: step t
+ * reads K[t+1] and V[t], writes K[t+2] and V[t+1] (staged through registers) and issues the
+ * global loads of K[t+3] and V[t+2].  Both K and V are double buffered, one barrier per step.
  *
  * Work order: blockIdx -> (XCD, slot).  Consecutive workgroup ids land on different XCDs, each
  * with its own L2; slot k of XCD x takes query head k%g of super-item (k/g)*8 + x, where a
@@ -53,6 +57,94 @@ __device__ __forceinline__ int attn_tile_block(const int32_t *list, int t, int I
     if (!SPARSE) return t >> 1;
     const int b = list[t >> 1];
     return b < 0 ? 0 : (b > I ? I : b);
+}
+
+// S^T (64 keys x 32 queries) of one K tile: s0 = keys 0..31, s1 = keys 32..63.
+__device__ __forceinline__ void attn_qk(const char *ktile, const bf16x8 (&qb)[8], f32x16 &s0, f32x16 &s1) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ktile + ks * 32);
+        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(ktile + 32 * kAttnKStride + ks * 32);
+        s0 = mfma32(a0, qb[ks], s0);
+        s1 = mfma32(a1, qb[ks], s1);
+    }
+}
+
+// Causal mask of a diagonal tile: key 8(i/4) + i%4 (+32 for s1) is in this lane's future if it
+// exceeds lim = query - tile offset - 4*half.
+__device__ __forceinline__ void attn_mask(f32x16 &s0, f32x16 &s1, int lim) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int kk = 8 * (i >> 2) + (i & 3);
+        if (kk > lim) s0[i] = -INFINITY;
+        if (kk + 32 > lim) s1[i] = -INFINITY;
+    }
+}
+
+// Row max of one tile's S^T: 32 of the 64 keys are in this lane, the rest in lane^32.
+__device__ __forceinline__ float attn_rowmax(const f32x16 &s0, const f32x16 &s1) {
+    float ta = max3(s0[0], s0[1], s0[2]), tb = max3(s1[0], s1[1], s1[2]);
+#pragma unroll
+    for (int i = 3; i < 15; i += 2) {
+        ta = max3(ta, s0[i], s0[i + 1]);
+        tb = max3(tb, s1[i], s1[i + 1]);
+    }
+    const float tm = max3(ta, s0[15], fmaxf(tb, s1[15]));
+    return fmaxf(tm, __shfl_xor(tm, 32));
+}
+
+// Online-softmax bookkeeping for a new tile max: the accumulator and the row sum are rescaled
+// only when some row's max moved (wave-uniform test).
+__device__ __forceinline__ void attn_new_max(float tm, float c, float &m_run, float &l_run, f32x16 (&acc)[4]) {
+    const float m_new = fmaxf(m_run, tm);
+    if (__ballot(m_new > m_run)) {
+        const float a = fast_exp2((m_run - m_new) * c);
+        l_run *= a;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[dt][i] *= a;
+        m_run = m_new;
+    }
+}
+
+// p = 2^(c*s - c*m) rounded to bf16, laid out as the B operand of the PV product; the row sum is
+// taken over the rounded values (the ones that multiply V), two per VALU op.
+__device__ __forceinline__ void attn_exp(const f32x16 &s0, const f32x16 &s1, float c, float mc, float &l_run,
+                                         bf16x8 (&pb)[2][2]) {
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+        bf16x2 a, b;
+        a[0] = (__bf16)fast_exp2(__builtin_fmaf(s0[i], c, -mc));
+        a[1] = (__bf16)fast_exp2(__builtin_fmaf(s0[i + 1], c, -mc));
+        b[0] = (__bf16)fast_exp2(__builtin_fmaf(s1[i], c, -mc));
+        b[1] = (__bf16)fast_exp2(__builtin_fmaf(s1[i + 1], c, -mc));
+        l_run = add_pair(a, l_run);
+        l_run = add_pair(b, l_run);
+        pb[0][i >> 3][i & 7] = a[0];
+        pb[0][i >> 3][(i & 7) + 1] = a[1];
+        pb[1][i >> 3][i & 7] = b[0];
+        pb[1][i >> 3][(i & 7) + 1] = b[1];
+    }
+}
+
+// O^T += V^T P^T for one 64-key tile: V^T fragments by transpose reads of the row-major V tile.
+__device__ __forceinline__ void attn_pv(const char *vtile, const bf16x8 (&pb)[2][2], f32x16 (&acc)[4]) {
+#pragma unroll
+    for (int kt2 = 0; kt2 < 2; ++kt2)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const char *vp = vtile + (32 * kt2 + 16 * j) * kAttnVStride;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                const s16x4 lo = lds_read_tr(vp + dt * 64);
+                const s16x4 hi = lds_read_tr(vp + 8 * kAttnVStride + dt * 64);
+                const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                acc[dt] = mfma32(__builtin_bit_cast(bf16x8, a), pb[kt2][j], acc[dt]);
+            }
+        }
 }
 
 template <bool SPARSE>
@@ -75,6 +167,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     const int last_tok = bi.w - 1;
 
     const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, half = l >> 5;
+    const int q_local = 32 * w + (l & 31);
 
     int nb = I + 1;
     const int32_t *list = nullptr;
@@ -85,68 +178,6 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     }
     const int ntiles = 2 * nb;
 
-#define FP_TILE_BLOCK(t) attn_tile_block<SPARSE>(list, (t), I)
-
-    // Q^T B-fragments: query 32w + l%32, dims 16ks + 8*half..+7.
-    bf16x8 qb[8];
-    {
-        int row = 32 * w + (l & 31);
-        row = row < bi.y ? row : bi.y - 1;
-        const uint16_t *qp = Q + ((size_t)(bi.x + row) * hq + h) * kHeadDim + 8 * half;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qb[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
-    }
-
-    // Staging: thread (row = tid/16 + 16i, chunk = tid%16) moves 16 bytes of K and of V.
-    u32x4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
-    const int st_row = tid >> 4, st_chunk = tid & 15;
-    // Loads use a wave-uniform base (first token of the tile, KV head) plus a per-thread 32-bit
-    // byte offset, so the address is one scalar pair + one VGPR.  Only a tile that reaches past
-    // the end of its sequence (ragged last block) needs per-row clamping.
-    const uint32_t row_bytes = (uint32_t)hkv * kHeadDim * 2;
-    const uint32_t st_off = (uint32_t)st_row * row_bytes + (uint32_t)st_chunk * 16;
-    const char *Kb = reinterpret_cast<const char *>(K) + (size_t)hk * kHeadDim * 2;
-    const char *Vb = reinterpret_cast<const char *>(V) + (size_t)hk * kHeadDim * 2;
-#define FP_LOAD_ROW(i_, kr_, vr_)                                                                         \
-    {                                                                                                     \
-        uint32_t o_ = st_off + 16u * (i_) * row_bytes;                                                    \
-        if (ragged_) {                                                                                    \
-            int tok_ = tok0_ + st_row + 16 * (i_);                                                        \
-            tok_ = tok_ < last_tok ? tok_ : last_tok; /* keys past the end are masked as future keys */   \
-            o_ = (uint32_t)(tok_ - base_tok_) * row_bytes + (uint32_t)st_chunk * 16; /* tok_ >= base_tok_ */ \
-        }                                                                                                 \
-        kr_ = *reinterpret_cast<const u32x4 *>(kbase_ + o_);                                              \
-        vr_ = *reinterpret_cast<const u32x4 *>(vbase_ + o_);                                              \
-    }
-#define FP_LOAD_TILE(t)                                                                                   \
-    do {                                                                                                  \
-        const int tok0_ = seq_tok0 + FP_TILE_BLOCK(t) * kBlock + ((t) & 1) * kAttnTileKeys;               \
-        const bool ragged_ = tok0_ + kAttnTileKeys - 1 > last_tok;                                        \
-        /* the base never lies past the sequence end, so the unsigned row offsets cannot wrap */          \
-        const int base_tok_ = tok0_ < last_tok ? tok0_ : last_tok;                                        \
-        const char *kbase_ = Kb + (size_t)base_tok_ * row_bytes;                                          \
-        const char *vbase_ = Vb + (size_t)base_tok_ * row_bytes;                                          \
-        FP_LOAD_ROW(0, kr0, vr0) FP_LOAD_ROW(1, kr1, vr1) FP_LOAD_ROW(2, kr2, vr2) FP_LOAD_ROW(3, kr3, vr3) \
-    } while (0)
-#define FP_STORE_ROW(i_, kr_, vr_)                                                                        \
-    *reinterpret_cast<u32x4 *>(kd_ + 16 * (i_) * kAttnKStride) = kr_;                                     \
-    *reinterpret_cast<u32x4 *>(vd_ + 16 * (i_) * kAttnVStride) = vr_;
-#define FP_STORE_TILE(buf)                                                                                \
-    do {                                                                                                  \
-        char *kd_ = smem + (buf) * kAttnKTile + st_row * kAttnKStride + st_chunk * 16;                    \
-        char *vd_ = smem + 2 * kAttnKTile + (buf) * kAttnVTile + st_row * kAttnVStride + st_chunk * 16;   \
-        FP_STORE_ROW(0, kr0, vr0) FP_STORE_ROW(1, kr1, vr1) FP_STORE_ROW(2, kr2, vr2) FP_STORE_ROW(3, kr3, vr3) \
-    } while (0)
-
-    f32x16 acc[4];
-#pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
-    float m_run = -INFINITY;   // running row max of the raw dot products (before scaling by c)
-    float l_run = 0.f;         // this lane's share of the running row sum
-
-    const int q_local = 32 * w + (l & 31);
     if (ntiles == 0) {   // empty list: O = 0, lse = -inf (uniform exit, before any barrier)
         if (q_local < bi.y) {
             uint16_t *op = O + ((size_t)(bi.x + q_local) * hq + h) * kHeadDim + 64 * half;
@@ -157,101 +188,145 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
         }
         return;
     }
-    FP_LOAD_TILE(0);
-    // Pin the Q fragments here: the loads must have landed before the tile loop, otherwise the
-    // compiler keeps a wait on vector-memory loads inside the loop's MFMA section, which in steady
-    // state would wait for the K/V prefetch issued moments earlier.
+
+#define FP_TILE_BLOCK(t) attn_tile_block<SPARSE>(list, (t), I)
+
+    // Q^T B-fragments: query 32w + l%32, dims 16ks + 8*half..+7.
+    bf16x8 qb[8];
+    {
+        int row = q_local < bi.y ? q_local : bi.y - 1;
+        const uint16_t *qp = Q + ((size_t)(bi.x + row) * hq + h) * kHeadDim + 8 * half;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[ks]));
-    FP_STORE_TILE(0);
-    if (ntiles > 1) FP_LOAD_TILE(1);
-    __syncthreads();
+        for (int ks = 0; ks < 8; ++ks) qb[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
+    }
+
+    // Staging: thread (row = tid/16 + 16i, chunk = tid%16) moves 16 bytes per row of a tile.
+    // Loads use a wave-uniform base (first token of the tile, KV head) plus a per-thread 32-bit
+    // byte offset, so an address is one scalar pair + one VGPR.  Only a tile that reaches past
+    // the end of its sequence (ragged last block) needs per-row clamping; its base is clamped
+    // too, so the unsigned row offsets can never wrap.
+    u32x4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
+    const int st_row = tid >> 4, st_chunk = tid & 15;
+    const uint32_t row_bytes = (uint32_t)hkv * kHeadDim * 2;
+    const uint32_t st_off = (uint32_t)st_row * row_bytes + (uint32_t)st_chunk * 16;
+    const char *Kb = reinterpret_cast<const char *>(K) + (size_t)hk * kHeadDim * 2;
+    const char *Vb = reinterpret_cast<const char *>(V) + (size_t)hk * kHeadDim * 2;
+#define FP_LOAD_ROW(i_, r_)                                                                               \
+    {                                                                                                     \
+        uint32_t o_ = st_off + 16u * (i_) * row_bytes;                                                    \
+        if (ragged_) {                                                                                    \
+            int tok_ = tok0_ + st_row + 16 * (i_);                                                        \
+            tok_ = tok_ < last_tok ? tok_ : last_tok; /* keys past the end are masked as future keys */   \
+            o_ = (uint32_t)(tok_ - base_tok_) * row_bytes + (uint32_t)st_chunk * 16; /* tok_ >= base_tok_ */ \
+        }                                                                                                 \
+        r_ = *reinterpret_cast<const u32x4 *>(base_ + o_);                                                \
+    }
+#define FP_LOAD(FULL, Xb, t, r0_, r1_, r2_, r3_)                                                          \
+    do {                                                                                                  \
+        const int tok0_ = seq_tok0 + FP_TILE_BLOCK(t) * kBlock + ((t) & 1) * kAttnTileKeys;               \
+        const bool ragged_ = !(FULL) && tok0_ + kAttnTileKeys - 1 > last_tok;                             \
+        const int base_tok_ = tok0_ < last_tok ? tok0_ : last_tok;                                        \
+        const char *base_ = Xb + (size_t)base_tok_ * row_bytes;                                           \
+        FP_LOAD_ROW(0, r0_) FP_LOAD_ROW(1, r1_) FP_LOAD_ROW(2, r2_) FP_LOAD_ROW(3, r3_)                   \
+    } while (0)
+    // FULL: the tile is known to lie in a block before the diagonal one, hence complete.
+#define FP_LOAD_K(FULL, t) FP_LOAD(FULL, Kb, t, kr0, kr1, kr2, kr3)
+#define FP_LOAD_V(FULL, t) FP_LOAD(FULL, Vb, t, vr0, vr1, vr2, vr3)
+#define FP_STORE_K(buf)                                                                                   \
+    do {                                                                                                  \
+        char *d_ = smem + (buf) * kAttnKTile + st_row * kAttnKStride + st_chunk * 16;                     \
+        *reinterpret_cast<u32x4 *>(d_) = kr0;                                                             \
+        *reinterpret_cast<u32x4 *>(d_ + 16 * kAttnKStride) = kr1;                                         \
+        *reinterpret_cast<u32x4 *>(d_ + 32 * kAttnKStride) = kr2;                                         \
+        *reinterpret_cast<u32x4 *>(d_ + 48 * kAttnKStride) = kr3;                                         \
+    } while (0)
+#define FP_STORE_V(buf)                                                                                   \
+    do {                                                                                                  \
+        char *d_ = smem + 2 * kAttnKTile + (buf) * kAttnVTile + st_row * kAttnVStride + st_chunk * 16;    \
+        *reinterpret_cast<u32x4 *>(d_) = vr0;                                                             \
+        *reinterpret_cast<u32x4 *>(d_ + 16 * kAttnVStride) = vr1;                                         \
+        *reinterpret_cast<u32x4 *>(d_ + 32 * kAttnVStride) = vr2;                                         \
+        *reinterpret_cast<u32x4 *>(d_ + 48 * kAttnVStride) = vr3;                                         \
+    } while (0)
+
+    f32x16 acc[4];
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
+    float m_run = -INFINITY;   // running row max of the raw dot products (before scaling by c)
+    float l_run = 0.f;         // this lane's share of the running row sum
 
     const int k_frag = (l & 31) * kAttnKStride + half * 16;
     // transpose-read base: row 4*half + (l%16)/4, dims 16*((l%32)/16) + 4*(l%4)
     const int v_frag = 2 * kAttnKTile + (4 * half + ((l & 15) >> 2)) * kAttnVStride + (16 * ((l & 31) >> 4) + 4 * (l & 3)) * 2;
+    // A tile of the diagonal block that lies wholly in this wave's future is skipped.
+#define FP_SKIP(t) (FP_TILE_BLOCK(t) == I && ((t) & 1) * kAttnTileKeys > 32 * w + 31)
 
-    for (int t = 0; t < ntiles; ++t) {
-        const int cur = t & 1;
-        if (t + 1 < ntiles) FP_STORE_TILE(cur ^ 1);
-        if (t + 2 < ntiles) FP_LOAD_TILE(t + 2);
+    // Prologue = step -1: K[0] and V[0] into LDS, loads of K[1] and V[1], S^T of tile 0 with its
+    // row max applied, K[1] into LDS, load of K[2].
+    FP_LOAD_K(false, 0);
+    FP_LOAD_V(false, 0);
+    // Pin the Q fragments here: their loads must have landed before the tile loop, otherwise the
+    // compiler keeps waits on vector-memory loads between the loop's MFMAs, which in steady state
+    // would wait for the K/V prefetch issued moments earlier.
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[ks]));
+    FP_STORE_K(0);
+    FP_STORE_V(0);
+    if (ntiles > 1) {
+        FP_LOAD_K(false, 1);
+        FP_LOAD_V(false, 1);
+    }
+    __syncthreads();
+    f32x16 sA0, sA1, sB0, sB1;
+    attn_qk(smem + k_frag, qb, sA0, sA1);   // tile 0 is never skipped (it starts at or before every query)
+    if (FP_TILE_BLOCK(0) == I) attn_mask(sA0, sA1, q_local - 4 * half);
+    m_run = attn_rowmax(sA0, sA1);          // finite: key 0 of tile 0 is visible to every query
+    if (ntiles > 1) FP_STORE_K(1);
+    if (ntiles > 2) FP_LOAD_K(false, 2);
+    __syncthreads();
 
-        const int koff = (t & 1) * kAttnTileKeys;
-        const bool diag = FP_TILE_BLOCK(t) == I;
-        if (!(diag && koff > 32 * w + 31)) {   // a diagonal tile wholly in this wave's future is skipped
-            f32x16 s0, s1;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
-            const char *kt = smem + cur * kAttnKTile + k_frag;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(kt + ks * 32);
-                const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(kt + 32 * kAttnKStride + ks * 32);
-                s0 = mfma32(a0, qb[ks], s0);
-                s1 = mfma32(a1, qb[ks], s1);
-            }
-            if (diag) {
-                // key (koff + 32kt + 8(i/4) + 4half + i%4) is in the future of query q_local
-                const int lim = q_local - koff - 4 * half;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int kk = 8 * (i >> 2) + (i & 3);
-                    if (kk > lim) s0[i] = -INFINITY;
-                    if (kk + 32 > lim) s1[i] = -INFINITY;
-                }
-            }
-            float ta = max3(s0[0], s0[1], s0[2]), tb = max3(s1[0], s1[1], s1[2]);
-#pragma unroll
-            for (int i = 3; i < 15; i += 2) {
-                ta = max3(ta, s0[i], s0[i + 1]);
-                tb = max3(tb, s1[i], s1[i + 1]);
-            }
-            float tm = max3(ta, s0[15], max3(tb, s1[15], s1[15]));
-            tm = fmaxf(tm, __shfl_xor(tm, 32));
-            const float m_new = fmaxf(m_run, tm);
-            if (__ballot(m_new > m_run)) {
-                const float a = fast_exp2((m_run - m_new) * c);
-                l_run *= a;
-#pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[dt][i] *= a;
-                m_run = m_new;
-            }
-            const float mc = m_run * c;
-            // p = 2^(c*s - c*m), rounded to bf16 for the PV product; the row sum is taken over the
-            // rounded values (the ones that multiply V), two per VALU op.
-            bf16x8 pb[2][2];
-#pragma unroll
-            for (int i = 0; i < 16; i += 2) {
-                bf16x2 a, b;
-                a[0] = (__bf16)fast_exp2(__builtin_fmaf(s0[i], c, -mc));
-                a[1] = (__bf16)fast_exp2(__builtin_fmaf(s0[i + 1], c, -mc));
-                b[0] = (__bf16)fast_exp2(__builtin_fmaf(s1[i], c, -mc));
-                b[1] = (__bf16)fast_exp2(__builtin_fmaf(s1[i + 1], c, -mc));
-                l_run = add_pair(a, l_run);
-                l_run = add_pair(b, l_run);
-                pb[0][i >> 3][i & 7] = a[0];
-                pb[0][i >> 3][(i & 7) + 1] = a[1];
-                pb[1][i >> 3][i & 7] = b[0];
-                pb[1][i >> 3][(i & 7) + 1] = b[1];
-            }
-            const char *vt = smem + cur * kAttnVTile + v_frag;
-#pragma unroll
-            for (int kt2 = 0; kt2 < 2; ++kt2)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) {
-                    const char *vp = vt + (32 * kt2 + 16 * j) * kAttnVStride;
-#pragma unroll
-                    for (int dt = 0; dt < 4; ++dt) {
-                        const s16x4 lo = lds_read_tr(vp + dt * 64);
-                        const s16x4 hi = lds_read_tr(vp + 8 * kAttnVStride + dt * 64);
-                        const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                        acc[dt] = mfma32(__builtin_bit_cast(bf16x8, a), pb[kt2][j], acc[dt]);
-                    }
-                }
-        }
-        __syncthreads();
+    // Step t.  On entry: K[t+1] and V[t] are in LDS, the staging registers hold K[t+2] and V[t+1],
+    // S^T(t) is in (c0, c1) and its row max is already folded into m_run (accumulator rescaled).
+    // PLAIN steps carry no guard at all (tiles t .. t+3 all lie before the diagonal block, so every
+    // prefetch exists and is a complete tile), so the whole step is one basic block and the scheduler can interleave the QK^T MFMAs of
+    // tile t+1 with the exponentials of tile t, and the PV MFMAs of tile t with the max of t+1.
+#define FP_STEP(PLAIN, t, c0, c1, n0, n1)                                                                 \
+    do {                                                                                                  \
+        const int t_ = (t);                                                                               \
+        if (PLAIN || t_ + 2 < ntiles) FP_STORE_K(t_ & 1);                                                 \
+        if (PLAIN || t_ + 1 < ntiles) FP_STORE_V((t_ + 1) & 1);                                           \
+        if (PLAIN || t_ + 3 < ntiles) FP_LOAD_K(PLAIN, t_ + 3);                                                \
+        if (PLAIN || t_ + 2 < ntiles) FP_LOAD_V(PLAIN, t_ + 2);                                                \
+        const bool do_cur_ = PLAIN || !FP_SKIP(t_);                                                       \
+        const bool do_nxt_ = PLAIN || (t_ + 1 < ntiles && !FP_SKIP(t_ + 1));                              \
+        bf16x8 pb_[2][2];                                                                                 \
+        if (do_cur_) attn_exp(c0, c1, c, m_run * c, l_run, pb_);                                          \
+        if (do_nxt_) attn_qk(smem + ((t_ + 1) & 1) * kAttnKTile + k_frag, qb, n0, n1);                    \
+        if (do_cur_) attn_pv(smem + (t_ & 1) * kAttnVTile + v_frag, pb_, acc);                            \
+        if (do_nxt_) {                                                                                    \
+            if (!PLAIN && FP_TILE_BLOCK(t_ + 1) == I)                                                     \
+                attn_mask(n0, n1, q_local - ((t_ + 1) & 1) * kAttnTileKeys - 4 * half);                   \
+            attn_new_max(attn_rowmax(n0, n1), c, m_run, l_run, acc);                                      \
+        }                                                                                                 \
+        __syncthreads();                                                                                  \
+    } while (0)
+
+    // Tiles before the diagonal block are plain (and complete: only a sequence's last block can be
+    // partial, and a row only meets it as its diagonal); the list is ascending, so only its last
+    // block can be the diagonal one.  A plain step t needs tiles t .. t+3 plain.
+    const int n_plain = FP_TILE_BLOCK(ntiles - 1) == I ? ntiles - 2 : ntiles;
+    const int t_main = (n_plain - 3) & ~1;   // even count of plain steps (negative: none)
+    int t = 0;
+    for (; t < t_main; t += 2) {
+        FP_STEP(true, t, sA0, sA1, sB0, sB1);
+        FP_STEP(true, t + 1, sB0, sB1, sA0, sA1);
+    }
+    for (; t < ntiles; t += 2) {
+        FP_STEP(false, t, sA0, sA1, sB0, sB1);
+        if (t + 1 >= ntiles) break;
+        FP_STEP(false, t + 1, sB0, sB1, sA0, sA1);
     }
 
     // O = acc / l, lse = m + log2 l (Alg. 3, final normalisation); rows past a ragged end are not stored.
@@ -272,10 +347,14 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
             lse[(size_t)h * T + bi.x + q_local] = l_tot > 0.f ? m_run * c + __log2f(l_tot) : -INFINITY;
     }
 #undef FP_TILE_BLOCK
-#undef FP_LOAD_TILE
-#undef FP_STORE_TILE
 #undef FP_LOAD_ROW
-#undef FP_STORE_ROW
+#undef FP_LOAD
+#undef FP_LOAD_K
+#undef FP_LOAD_V
+#undef FP_STORE_K
+#undef FP_STORE_V
+#undef FP_SKIP
+#undef FP_STEP
 }
 
 }  // namespace fp
