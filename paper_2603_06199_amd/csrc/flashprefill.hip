@@ -149,6 +149,10 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
     ok = ok && hipMemcpy(p->d_order, order.data(), order.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds) == hipSuccess;
     (void)hipSetDevice(prev);
     if (!ok) {
         (void)hipGetLastError();
@@ -205,10 +209,10 @@ static fp_status launch_attn(fp_plan *p, bool sparse, const void *Q, const void 
                    *v = static_cast<const uint16_t *>(V);
     uint16_t *o = static_cast<uint16_t *>(O);
     if (sparse)
-        fp::attn_kernel<true><<<dim3(grid), 256, 0, st>>>(q, k, v, idx, cnt, p->d_blk, p->d_order, p->m_total, p->n_max,
+        fp::attn_kernel<true><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, idx, cnt, p->d_blk, p->d_order, p->m_total, p->n_max,
                                                            p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     else
-        fp::attn_kernel<false><<<dim3(grid), 256, 0, st>>>(q, k, v, nullptr, nullptr, p->d_blk, p->d_order, p->m_total,
+        fp::attn_kernel<false><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, nullptr, nullptr, p->d_blk, p->d_order, p->m_total,
                                                             p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     return launch_status();
 }

@@ -5,15 +5,19 @@
 
 namespace fp {
 
-// LDS tiles of 64 keys.  K rows are padded to 272 bytes so that the 16-byte A-fragment reads of
-// 16 consecutive rows fall on 16 distinct 4-bank groups; V rows are padded to 320 bytes so that
-// the 4 rows a transpose read touches per lane group fall on 4 distinct 16-bank groups.
+// LDS: three K buffers and two V buffers of one 64-key tile (64 rows x 256 B, unpadded) each.
+// Tiles are written by direct global->LDS loads (16 B per lane, lane i lands at base + 16 i), so
+// bank conflicts are avoided by permuting the 16-byte chunks inside a row instead of padding:
+//   K row r keeps chunk c at position c ^ (r & 15): the A-fragment reads of 16 consecutive rows
+//     at one chunk index then hit 16 different bank groups;
+//   V row r keeps chunk c at position c ^ 4 (r & 3): the four rows a transpose read touches per
+//     lane group then hit four different 64-byte bank groups.
 constexpr int kAttnTileKeys = 64;
-constexpr int kAttnKStride = 272;
-constexpr int kAttnVStride = 320;
-constexpr int kAttnKTile = kAttnTileKeys * kAttnKStride;   // 17408
-constexpr int kAttnVTile = kAttnTileKeys * kAttnVStride;   // 20480
-constexpr int kAttnLds = 2 * kAttnKTile + 2 * kAttnVTile;  // 75776: two workgroups per CU
+constexpr int kAttnRowBytes = 256;
+constexpr int kAttnTile = kAttnTileKeys * kAttnRowBytes;   // 16384
+constexpr int kAttnKBufs = 3, kAttnVBufs = 2;
+constexpr int kAttnVBase = kAttnKBufs * kAttnTile;
+constexpr int kAttnLds = (kAttnKBufs + kAttnVBufs) * kAttnTile;   // 81920: two workgroups per CU
 
 // ds_read_b64_tr_b16: within each group of 16 lanes the 16 x 4 b16 values addressed by the
 // lanes (lane j supplies 4 consecutive b16) are exchanged so that lane i receives, in element e,
@@ -23,6 +27,22 @@ constexpr int kAttnLds = 2 * kAttnKTile + 2 * kAttnVTile;  // 75776: two workgro
 __device__ __forceinline__ s16x4 lds_read_tr(const char *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4i16((FP_LDS(s16x4) *)(FP_LDS(char) *)p);
 }
+
+// 16 bytes per lane, global -> LDS, no register staging: lane i's 16 bytes, fetched from
+// sbase + voff, land at LDS byte address lds_addr + 16 i (lds_addr is wave-uniform and goes to
+// M0).  Written as inline assembly on purpose: the compiler then neither tracks these loads in
+// vmcnt nor orders LDS reads after them (it would wait for *all* outstanding loads before the
+// first LDS read of every step, which defeats the prefetch).  Completion is waited for
+// explicitly with FP_WAIT_VMCNT followed by a workgroup barrier.
+__device__ __forceinline__ void load_to_lds(const char *sbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_addr)
+                 : "memory");
+}
+
+// s_waitcnt vmcnt(n) alone (expcnt and lgkmcnt left at "no wait"), n < 16
+#define FP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | (n))
 
 /*
  * One workgroup (4 waves) per (query head, q-block row); wave w owns queries 32w..32w+31 of the
@@ -43,8 +63,8 @@ __device__ __forceinline__ s16x4 lds_read_tr(const char *p) {
  * and only then runs the softmax of tile t (VALU) and the PV MFMAs of tile t, so the matrix
  * pipe works on t+1 while the vector ALU exponentiates t.  The S^T registers alternate between
  * two sets (steps are unrolled in pairs).  K therefore runs one tile ahead of V in LDS: step t
- * reads K[t+1] and V[t], writes K[t+2] and V[t+1] (staged through registers) and issues the
- * global loads of K[t+3] and V[t+2].  Both K and V are double buffered, one barrier per step.
+ * reads K[t+1] and V[t] and issues the direct-to-LDS loads of V[t+1] and K[t+3]; K has three
+ * buffers, V two; one barrier per step.
  *
  * Work order: blockIdx -> (XCD, slot).  Consecutive workgroup ids land on different XCDs, each
  * with its own L2; slot k of XCD x takes query head k%g of super-item (k/g)*8 + x, where a
@@ -60,13 +80,15 @@ __device__ __forceinline__ int attn_tile_block(const int32_t *list, int t, int I
 }
 
 // S^T (64 keys x 32 queries) of one K tile: s0 = keys 0..31, s1 = keys 32..63.
-__device__ __forceinline__ void attn_qk(const char *ktile, const bf16x8 (&qb)[8], f32x16 &s0, f32x16 &s1) {
+// kaddr = buffer base + the lane's row and swizzled chunk for k-slice 0; slice ks sits at kaddr ^ (ks << 5).
+__device__ __forceinline__ void attn_qk(const char *smem, uint32_t kaddr, const bf16x8 (&qb)[8], f32x16 &s0, f32x16 &s1) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) {
-        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(ktile + ks * 32);
-        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(ktile + 32 * kAttnKStride + ks * 32);
+        const char *kp = smem + (kaddr ^ (uint32_t)(ks << 5));
+        const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(kp);
+        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(kp + 32 * kAttnRowBytes);
         s0 = mfma32(a0, qb[ks], s0);
         s1 = mfma32(a1, qb[ks], s1);
     }
@@ -131,20 +153,21 @@ __device__ __forceinline__ void attn_exp(const f32x16 &s0, const f32x16 &s1, flo
 }
 
 // O^T += V^T P^T for one 64-key tile: V^T fragments by transpose reads of the row-major V tile.
-__device__ __forceinline__ void attn_pv(const char *vtile, const bf16x8 (&pb)[2][2], f32x16 (&acc)[4]) {
+// vaddr[dt] = buffer base + the lane's row/column offsets with the swizzle of d-tile dt folded in.
+__device__ __forceinline__ void attn_pv(const char *smem, const uint32_t (&vaddr)[4], const bf16x8 (&pb)[2][2],
+                                        f32x16 (&acc)[4]) {
 #pragma unroll
     for (int kt2 = 0; kt2 < 2; ++kt2)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const char *vp = vtile + (32 * kt2 + 16 * j) * kAttnVStride;
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
-                const s16x4 lo = lds_read_tr(vp + dt * 64);
-                const s16x4 hi = lds_read_tr(vp + 8 * kAttnVStride + dt * 64);
+                const char *vp = smem + vaddr[dt] + (32 * kt2 + 16 * j) * kAttnRowBytes;
+                const s16x4 lo = lds_read_tr(vp);
+                const s16x4 hi = lds_read_tr(vp + 8 * kAttnRowBytes);
                 const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 acc[dt] = mfma32(__builtin_bit_cast(bf16x8, a), pb[kt2][j], acc[dt]);
             }
-        }
 }
 
 template <bool SPARSE>
@@ -153,7 +176,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     const int32_t *__restrict__ idx, const int32_t *__restrict__ cnt, const BlockRec *__restrict__ blk,
     const int32_t *__restrict__ order, int m_total, int n_max, int hq, int hkv, int g, int T, float c,
     uint16_t *__restrict__ O, float *__restrict__ lse) {
-    __shared__ __attribute__((aligned(16))) char smem[kAttnLds];
+    extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int x = blockIdx.x & 7, k = blockIdx.x >> 3;
     const int s = (k / g) * 8 + x, hg = k % g;
@@ -166,7 +189,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     const int seq_tok0 = bi.x - I * kBlock;
     const int last_tok = bi.w - 1;
 
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63, half = l >> 5;
+    const int tid = threadIdx.x, l = tid & 63, half = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, held in a scalar register
     const int q_local = 32 * w + (l & 31);
 
     int nb = I + 1;
@@ -200,54 +224,48 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
         for (int ks = 0; ks < 8; ++ks) qb[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
     }
 
-    // Staging: thread (row = tid/16 + 16i, chunk = tid%16) moves 16 bytes per row of a tile.
-    // Loads use a wave-uniform base (first token of the tile, KV head) plus a per-thread 32-bit
-    // byte offset, so an address is one scalar pair + one VGPR.  Only a tile that reaches past
+    // Tile loads.  One wave-wide instruction moves 4 rows (1 KB); wave w loads rows 16w + 4i + l/16
+    // (i = 0..3) of a K or V tile.  Lane l fills LDS position l%16 of its row, i.e. it fetches the
+    // global chunk (l%16) ^ swizzle(row).  The global address is a wave-uniform base (first token
+    // of the tile, KV head) plus a per-lane 32-bit byte offset.  Only a tile that reaches past
     // the end of its sequence (ragged last block) needs per-row clamping; its base is clamped
     // too, so the unsigned row offsets can never wrap.
-    u32x4 kr0, kr1, kr2, kr3, vr0, vr1, vr2, vr3;
-    const int st_row = tid >> 4, st_chunk = tid & 15;
     const uint32_t row_bytes = (uint32_t)hkv * kHeadDim * 2;
-    const uint32_t st_off = (uint32_t)st_row * row_bytes + (uint32_t)st_chunk * 16;
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(FP_LDS(char) *)smem;
+    const int ld_row = 16 * w + (l >> 4);   // + 4i
+    const int ld_pos = l & 15;
     const char *Kb = reinterpret_cast<const char *>(K) + (size_t)hk * kHeadDim * 2;
     const char *Vb = reinterpret_cast<const char *>(V) + (size_t)hk * kHeadDim * 2;
-#define FP_LOAD_ROW(i_, r_)                                                                               \
-    {                                                                                                     \
-        uint32_t o_ = st_off + 16u * (i_) * row_bytes;                                                    \
-        if (ragged_) {                                                                                    \
-            int tok_ = tok0_ + st_row + 16 * (i_);                                                        \
-            tok_ = tok_ < last_tok ? tok_ : last_tok; /* keys past the end are masked as future keys */   \
-            o_ = (uint32_t)(tok_ - base_tok_) * row_bytes + (uint32_t)st_chunk * 16; /* tok_ >= base_tok_ */ \
-        }                                                                                                 \
-        r_ = *reinterpret_cast<const u32x4 *>(base_ + o_);                                                \
+    uint32_t ld_kcol[4], ld_vcol[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int row = ld_row + 4 * i;
+        ld_kcol[i] = (uint32_t)((ld_pos ^ (row & 15)) * 16);
+        ld_vcol[i] = (uint32_t)((ld_pos ^ (4 * (row & 3))) * 16);
     }
-#define FP_LOAD(FULL, Xb, t, r0_, r1_, r2_, r3_)                                                          \
+#define FP_LOAD(FULL, Xb, col_, t, ldsoff_)                                                               \
     do {                                                                                                  \
         const int tok0_ = seq_tok0 + FP_TILE_BLOCK(t) * kBlock + ((t) & 1) * kAttnTileKeys;               \
         const bool ragged_ = !(FULL) && tok0_ + kAttnTileKeys - 1 > last_tok;                             \
         const int base_tok_ = tok0_ < last_tok ? tok0_ : last_tok;                                        \
         const char *base_ = Xb + (size_t)base_tok_ * row_bytes;                                           \
-        FP_LOAD_ROW(0, r0_) FP_LOAD_ROW(1, r1_) FP_LOAD_ROW(2, r2_) FP_LOAD_ROW(3, r3_)                   \
+        const uint32_t dst_ = lds_base + (ldsoff_) + 16 * w * kAttnRowBytes;                              \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                \
+            uint32_t ro_ = (uint32_t)(ld_row + 4 * i_) * row_bytes;                                       \
+            if (ragged_) {                                                                                \
+                int tok_ = tok0_ + ld_row + 4 * i_;                                                       \
+                tok_ = tok_ < last_tok ? tok_ : last_tok; /* keys past the end are masked as future */    \
+                ro_ = (uint32_t)(tok_ - base_tok_) * row_bytes; /* tok_ >= base_tok_ */                   \
+            }                                                                                             \
+            load_to_lds(base_, ro_ + col_[i_], dst_ + 4 * i_ * kAttnRowBytes);                            \
+        }                                                                                                 \
     } while (0)
     // FULL: the tile is known to lie in a block before the diagonal one, hence complete.
-#define FP_LOAD_K(FULL, t) FP_LOAD(FULL, Kb, t, kr0, kr1, kr2, kr3)
-#define FP_LOAD_V(FULL, t) FP_LOAD(FULL, Vb, t, vr0, vr1, vr2, vr3)
-#define FP_STORE_K(buf)                                                                                   \
-    do {                                                                                                  \
-        char *d_ = smem + (buf) * kAttnKTile + st_row * kAttnKStride + st_chunk * 16;                     \
-        *reinterpret_cast<u32x4 *>(d_) = kr0;                                                             \
-        *reinterpret_cast<u32x4 *>(d_ + 16 * kAttnKStride) = kr1;                                         \
-        *reinterpret_cast<u32x4 *>(d_ + 32 * kAttnKStride) = kr2;                                         \
-        *reinterpret_cast<u32x4 *>(d_ + 48 * kAttnKStride) = kr3;                                         \
-    } while (0)
-#define FP_STORE_V(buf)                                                                                   \
-    do {                                                                                                  \
-        char *d_ = smem + 2 * kAttnKTile + (buf) * kAttnVTile + st_row * kAttnVStride + st_chunk * 16;    \
-        *reinterpret_cast<u32x4 *>(d_) = vr0;                                                             \
-        *reinterpret_cast<u32x4 *>(d_ + 16 * kAttnVStride) = vr1;                                         \
-        *reinterpret_cast<u32x4 *>(d_ + 32 * kAttnVStride) = vr2;                                         \
-        *reinterpret_cast<u32x4 *>(d_ + 48 * kAttnVStride) = vr3;                                         \
-    } while (0)
+    // K tile t lives in K buffer t % 3, V tile t in V buffer t % 2.
+#define FP_KBUF(t) ((uint32_t)(((t) % kAttnKBufs) * kAttnTile))
+#define FP_VBUF(t) ((uint32_t)(kAttnVBase + ((t) & 1) * kAttnTile))
+#define FP_LOAD_K(FULL, t) FP_LOAD(FULL, Kb, ld_kcol, t, FP_KBUF(t))
+#define FP_LOAD_V(FULL, t) FP_LOAD(FULL, Vb, ld_vcol, t, FP_VBUF(t))
 
     f32x16 acc[4];
 #pragma unroll
@@ -257,59 +275,73 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     float m_run = -INFINITY;   // running row max of the raw dot products (before scaling by c)
     float l_run = 0.f;         // this lane's share of the running row sum
 
-    const int k_frag = (l & 31) * kAttnKStride + half * 16;
-    // transpose-read base: row 4*half + (l%16)/4, dims 16*((l%32)/16) + 4*(l%4)
-    const int v_frag = 2 * kAttnKTile + (4 * half + ((l & 15) >> 2)) * kAttnVStride + (16 * ((l & 31) >> 4) + 4 * (l & 3)) * 2;
+    // Fragment addresses inside a buffer.  K: rows l%32 and 32 + l%32, chunk (2ks + half) ^ (row & 15).
+    const int krow = l & 31;
+    const uint32_t k_frag =
+        (uint32_t)(krow * kAttnRowBytes + ((((krow >> 1) & 7) << 5) | ((half ^ (krow & 1)) << 4)));
+    // V transpose reads: row 32kt + 16j + 4half + e (+8), e = (l%16)/4 = row & 3; 8-byte unit at
+    // dims 32dt + 16gq + 4cc, i.e. chunk 4dt + 2gq + cc/2, stored at chunk ^ 4e = 4(dt ^ e) + ...
+    uint32_t v_frag[4];
+    {
+        const int e = (l & 15) >> 2, gq = (l & 31) >> 4, cc = l & 3;
+        const uint32_t vb = (uint32_t)((4 * half + e) * kAttnRowBytes + (2 * gq + (cc >> 1)) * 16 + 8 * (cc & 1));
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt) v_frag[dt] = vb + (uint32_t)((dt ^ e) * 64);
+    }
     // A tile of the diagonal block that lies wholly in this wave's future is skipped.
 #define FP_SKIP(t) (FP_TILE_BLOCK(t) == I && ((t) & 1) * kAttnTileKeys > 32 * w + 31)
 
-    // Prologue = step -1: K[0] and V[0] into LDS, loads of K[1] and V[1], S^T of tile 0 with its
-    // row max applied, K[1] into LDS, load of K[2].
+    // Prologue: K[0], V[0], K[1] landed, K[2] on its way; S^T of tile 0 with its row max.
     FP_LOAD_K(false, 0);
     FP_LOAD_V(false, 0);
-    // Pin the Q fragments here: their loads must have landed before the tile loop, otherwise the
-    // compiler keeps waits on vector-memory loads between the loop's MFMAs, which in steady state
-    // would wait for the K/V prefetch issued moments earlier.
+    // Pin the Q fragments: their loads are issued by now and are older than everything the loop
+    // waits for, so no wait on them can end up between the loop's MFMAs.
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[ks]));
-    FP_STORE_K(0);
-    FP_STORE_V(0);
-    if (ntiles > 1) {
-        FP_LOAD_K(false, 1);
-        FP_LOAD_V(false, 1);
+    if (ntiles > 1) FP_LOAD_K(false, 1);
+    if (ntiles > 2) {
+        FP_LOAD_K(false, 2);
+        FP_WAIT_VMCNT(4);
+    } else {
+        FP_WAIT_VMCNT(0);
     }
     __syncthreads();
     f32x16 sA0, sA1, sB0, sB1;
-    attn_qk(smem + k_frag, qb, sA0, sA1);   // tile 0 is never skipped (it starts at or before every query)
+    attn_qk(smem, FP_KBUF(0) + k_frag, qb, sA0, sA1);   // tile 0 is never skipped (it starts at or before every query)
     if (FP_TILE_BLOCK(0) == I) attn_mask(sA0, sA1, q_local - 4 * half);
-    m_run = attn_rowmax(sA0, sA1);          // finite: key 0 of tile 0 is visible to every query
-    if (ntiles > 1) FP_STORE_K(1);
-    if (ntiles > 2) FP_LOAD_K(false, 2);
-    __syncthreads();
+    m_run = attn_rowmax(sA0, sA1);                      // finite: key 0 of tile 0 is visible to every query
 
-    // Step t.  On entry: K[t+1] and V[t] are in LDS, the staging registers hold K[t+2] and V[t+1],
-    // S^T(t) is in (c0, c1) and its row max is already folded into m_run (accumulator rescaled).
-    // PLAIN steps carry no guard at all (tiles t .. t+3 all lie before the diagonal block, so every
-    // prefetch exists and is a complete tile), so the whole step is one basic block and the scheduler can interleave the QK^T MFMAs of
-    // tile t+1 with the exponentials of tile t, and the PV MFMAs of tile t with the max of t+1.
+    // Step t.  On entry K[t+1] and V[t] are complete in LDS, K[t+2] may still be landing, S^T(t) is
+    // in (c0, c1) and its row max is already folded into m_run (accumulator rescaled).  The step
+    // issues V[t+1] into the buffer V[t-1] used and K[t+3] into the buffer K[t] used (all waves are
+    // past step t-1's barrier, which was their last reader) and ends by waiting for everything but
+    // K[t+3].  PLAIN steps carry no guard at all (tiles t .. t+3 lie before the diagonal block, so
+    // every prefetch exists and is a complete tile): the step is one basic block and the scheduler
+    // can interleave the QK^T MFMAs of tile t+1 with the exponentials of tile t, and the PV MFMAs
+    // of tile t with the max of t+1.
 #define FP_STEP(PLAIN, t, c0, c1, n0, n1)                                                                 \
     do {                                                                                                  \
         const int t_ = (t);                                                                               \
-        if (PLAIN || t_ + 2 < ntiles) FP_STORE_K(t_ & 1);                                                 \
-        if (PLAIN || t_ + 1 < ntiles) FP_STORE_V((t_ + 1) & 1);                                           \
-        if (PLAIN || t_ + 3 < ntiles) FP_LOAD_K(PLAIN, t_ + 3);                                                \
-        if (PLAIN || t_ + 2 < ntiles) FP_LOAD_V(PLAIN, t_ + 2);                                                \
+        const bool more_ = PLAIN || t_ + 3 < ntiles;                                                      \
+        if (PLAIN || t_ + 1 < ntiles) FP_LOAD_V(PLAIN, t_ + 1);                                           \
+        if (more_) FP_LOAD_K(PLAIN, t_ + 3);                                                              \
         const bool do_cur_ = PLAIN || !FP_SKIP(t_);                                                       \
         const bool do_nxt_ = PLAIN || (t_ + 1 < ntiles && !FP_SKIP(t_ + 1));                              \
         bf16x8 pb_[2][2];                                                                                 \
         if (do_cur_) attn_exp(c0, c1, c, m_run * c, l_run, pb_);                                          \
-        if (do_nxt_) attn_qk(smem + ((t_ + 1) & 1) * kAttnKTile + k_frag, qb, n0, n1);                    \
-        if (do_cur_) attn_pv(smem + (t_ & 1) * kAttnVTile + v_frag, pb_, acc);                            \
+        if (do_nxt_) attn_qk(smem, FP_KBUF(t_ + 1) + k_frag, qb, n0, n1);                                 \
+        if (do_cur_) {                                                                                    \
+            uint32_t va_[4];                                                                              \
+            _Pragma("unroll") for (int dt_ = 0; dt_ < 4; ++dt_) va_[dt_] = FP_VBUF(t_) + v_frag[dt_];     \
+            attn_pv(smem, va_, pb_, acc);                                                                 \
+        }                                                                                                 \
         if (do_nxt_) {                                                                                    \
             if (!PLAIN && FP_TILE_BLOCK(t_ + 1) == I)                                                     \
                 attn_mask(n0, n1, q_local - ((t_ + 1) & 1) * kAttnTileKeys - 4 * half);                   \
             attn_new_max(attn_rowmax(n0, n1), c, m_run, l_run, acc);                                      \
         }                                                                                                 \
+        if (more_) FP_WAIT_VMCNT(4);                                                                      \
+        else FP_WAIT_VMCNT(0);                                                                            \
         __syncthreads();                                                                                  \
     } while (0)
 
@@ -347,12 +379,11 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
             lse[(size_t)h * T + bi.x + q_local] = l_tot > 0.f ? m_run * c + __log2f(l_tot) : -INFINITY;
     }
 #undef FP_TILE_BLOCK
-#undef FP_LOAD_ROW
 #undef FP_LOAD
 #undef FP_LOAD_K
 #undef FP_LOAD_V
-#undef FP_STORE_K
-#undef FP_STORE_V
+#undef FP_KBUF
+#undef FP_VBUF
 #undef FP_SKIP
 #undef FP_STEP
 }
