@@ -16,7 +16,9 @@
 
 namespace {
 
-constexpr int kMaxBlocksPerSeq = 4096;   // (m, S) of one row must fit the score kernel's LDS
+// (m, S) of one row for 2 heads must fit the score kernel's LDS next to its tile buffers
+// (2 x 16 KB + 1 KB + 2 x 8 B x blocks <= 160 KB would allow more; 4096 blocks = 512K tokens)
+constexpr int kMaxBlocksPerSeq = 4096;
 
 struct Layout {
     int m_total = 0, n_max = 0;
@@ -120,7 +122,7 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
     const float tau = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
     p->c = tau * fp::kLog2e;
     p->n_pad = (L.n_max + 31) / 32 * 32;
-    p->search_lds = (size_t)fp::kSearchStageBytes + (size_t)4 * p->n_pad * sizeof(float2);
+    p->search_lds = (size_t)fp::kSearchStageBytes + (size_t)fp::kSearchHeads * p->n_pad * sizeof(float2);
 
     std::vector<fp::BlockRec> blk((size_t)L.m_total);
     for (int s = 0; s < shape->nseq; ++s) {
@@ -177,7 +179,7 @@ fp_status fp_block_search(fp_plan *p, const void *Q, const void *K, float eps, f
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     fp::pool_k_kernel<<<dim3(p->m_total, p->hkv), 256, 0, st>>>(static_cast<const uint16_t *>(K), p->d_blk, p->hkv,
                                                                  p->d_kb_hi, p->d_kb_lo);
-    const int nchunk = (p->g + 3) / 4;
+    const int nchunk = (p->g + fp::kSearchHeads - 1) / fp::kSearchHeads;
     fp::search_kernel<<<dim3(p->m_total * p->hkv * nchunk), 256, p->search_lds, st>>>(
         static_cast<const uint16_t *>(Q), p->d_kb_hi, p->d_kb_lo, p->d_blk, p->d_order, p->m_total, p->n_max, p->n_pad,
         p->hq, p->hkv, p->g, nchunk, p->c, eps, scores);

@@ -59,4 +59,20 @@ __device__ __forceinline__ float add_pair(bf16x2 p, float acc) {
     return __builtin_amdgcn_fdot2_f32_bf16(p, ones, acc, false);
 }
 
+// 16 bytes per lane, global -> LDS, no register staging: lane i's 16 bytes, fetched from
+// sbase + voff, land at LDS byte address lds_addr + 16 i (lds_addr is wave-uniform and goes to
+// M0).  Written as inline assembly on purpose: the compiler then neither tracks these loads in
+// vmcnt nor orders LDS reads after them (it would wait for *all* outstanding loads before the
+// first LDS read of every step, which defeats the prefetch).  Completion is waited for
+// explicitly with FP_WAIT_VMCNT followed by a workgroup barrier.
+__device__ __forceinline__ void load_to_lds(const char *sbase, uint32_t voff, uint32_t lds_addr) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                 :
+                 : "v"(voff), "s"(sbase), "s"(lds_addr)
+                 : "memory");
+}
+
+// s_waitcnt vmcnt(n) alone (expcnt and lgkmcnt left at "no wait"), n < 16
+#define FP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | (n))
+
 }  // namespace fp

@@ -46,26 +46,95 @@ __global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict_
 }
 
 // ---------------------------------------------------------------------------------------------
-// Alg. 1 stages 2 and 3, fused.  One workgroup per (q-block row, KV head, group of 4 query
-// heads); wave w owns query head 4*chunk + w of the group and keeps that head's whole 128x128
-// query tile in registers as MFMA A-fragments (128 VGPRs).  Pooled keys stream through LDS in
-// tiles of 32 blocks (hi and lo planes, shared by the four waves, double buffered).  For each
-// tile a wave computes the 128 x 32 logits with 64 MFMAs (4 query sub-tiles x 8 k-slices x
-// {hi, lo}); the result layout puts one pooled key per lane column, so the reduction over the
-// query axis (Eq. 1-2: max, then sum of 2^(x - max)) is in-register plus one lane exchange.
-// (m, S) per block pair stay in LDS; after the last tile the wave takes the row max, rescales
-// (Eq. 3) and writes the normalised row (Eq. 4) once.  Nothing of size L x L/B ever exists.
+// Alg. 1 stages 2 and 3, fused.  One workgroup of 4 waves per (q-block row, KV head, pair of
+// query heads): wave w owns query head 2*chunk + w/2 of the group and queries 64*(w%2)..+63 of
+// the tile, kept in registers as MFMA A-fragments (64 VGPRs).  Pooled keys stream through LDS in
+// tiles of 32 blocks (hi and lo planes, shared by the four waves): direct global->LDS loads one
+// tile ahead into two swizzled, unpadded buffers.  For each tile a wave computes its 64 x 32
+// logits with 32 MFMAs (2 query sub-tiles x 8 k-slices x {hi, lo}); the result layout puts one
+// pooled key per lane column, so the reduction over the query axis (Eq. 1-2: max, then sum of
+// 2^(x - max)) is in-register plus one lane exchange.  The two waves of a head then merge their
+// (max, sum) pairs through a small LDS mailbox, one step later.  Registers and LDS leave room
+// for two to four workgroups per CU (up to about 2900 blocks per sequence for two): waves of
+// different workgroups share a SIMD without sharing a barrier, so one's MFMAs overlap the
+// other's reduction.  (m, S) per block pair stay in LDS; after the last
+// tile the row max is taken, the row rescaled (Eq. 3), normalised (Eq. 4) and written once.
+// Nothing of size L x L/B ever exists.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSearchKbStride = 272;                      // bytes per pooled-key row in LDS (256 + 16 pad)
-constexpr int kSearchPlane = 32 * kSearchKbStride;        // one plane (hi or lo) of a 32-row tile
-constexpr int kSearchStage = 2 * kSearchPlane;            // hi + lo
-constexpr int kSearchStageBytes = 2 * kSearchStage;       // double buffered
+constexpr int kSearchPlane = 32 * 256;                 // one plane (hi or lo) of a 32-row tile, unpadded
+constexpr int kSearchTile = 2 * kSearchPlane;          // hi + lo
+constexpr int kSearchBufs = 2;
+constexpr int kSearchHeads = 2;                        // query heads per workgroup
+constexpr int kSearchMailbox = 2 * kSearchHeads * 32 * 8;   // [step parity][head][pooled key] (max, sum)
+constexpr int kSearchStageBytes = kSearchBufs * kSearchTile + kSearchMailbox;
 
-__global__ __launch_bounds__(256, 1) void search_kernel(
+// 64 x 32 logits of one pooled-key tile: acc[qt] = Q[qt] (hi + lo)^T.  baddr = buffer base + the
+// lane's row and swizzled chunk for k-slice 0 (slice ks sits at baddr ^ (ks << 5)).
+__device__ __forceinline__ void search_mma(const char *smem, uint32_t baddr, const bf16x8 (&qa)[2][8], f32x16 (&acc)[2]) {
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[qt][i] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        const char *bp = smem + (baddr ^ (uint32_t)(ks << 5));
+        const bf16x8 bh = *reinterpret_cast<const bf16x8 *>(bp);
+        const bf16x8 bl = *reinterpret_cast<const bf16x8 *>(bp + kSearchPlane);
+        acc[0] = mfma32(qa[0][ks], bh, acc[0]);
+        acc[1] = mfma32(qa[1][ks], bh, acc[1]);
+        acc[0] = mfma32(qa[0][ks], bl, acc[0]);
+        acc[1] = mfma32(qa[1][ks], bl, acc[1]);
+    }
+}
+
+// Eq. 1-2 for the 32 pooled keys of a tile over this wave's 64 queries: per lane column, max and
+// sum of 2^(c x - c max); lanes l and l^32 hold the two halves of a column.  Queries at or past
+// nq (ragged last q-block; q0 = the wave's first query) are left out; a wave with no valid query
+// returns (-inf, 0), which the merge below treats as empty.
+template <bool RAGGED>
+__device__ __forceinline__ float2 search_reduce(f32x16 (&acc)[2], float c, int nq, int q0, int half) {
+    if (RAGGED) {
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i)
+                if (q0 + 32 * qt + 8 * (i >> 2) + 4 * half + (i & 3) >= nq) acc[qt][i] = -INFINITY;
+    }
+    float mx = max3(acc[0][0], acc[1][0], acc[0][1]);
+    mx = fmaxf(mx, acc[1][1]);
+#pragma unroll
+    for (int i = 2; i < 16; i += 2) {
+        mx = max3(mx, acc[0][i], acc[1][i]);
+        mx = max3(mx, acc[0][i + 1], acc[1][i + 1]);
+    }
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float mc = mx * c;
+    const float mcs = RAGGED ? (mx == -INFINITY ? 0.f : mc) : mc;   // all queries missing: every term is 2^-inf = 0
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        s0 += fast_exp2(__builtin_fmaf(acc[0][i], c, -mcs));
+        s1 += fast_exp2(__builtin_fmaf(acc[1][i], c, -mcs));
+    }
+    float sum = s0 + s1;
+    sum += __shfl_xor(sum, 32);
+    return make_float2(mc, sum);
+}
+
+// (max, sum) of the union of two query sets: bring both sums to the common max.
+__device__ __forceinline__ float2 search_merge(float2 a, float2 b) {
+    const float m = fmaxf(a.x, b.x);
+    const float sa = a.y > 0.f ? a.y * fast_exp2(a.x - m) : 0.f;
+    const float sb = b.y > 0.f ? b.y * fast_exp2(b.x - m) : 0.f;
+    return make_float2(m, sa + sb);
+}
+
+__global__ __launch_bounds__(256, 4) void search_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ kb_hi, const uint16_t *__restrict__ kb_lo,
     const BlockRec *__restrict__ blk, const int32_t *__restrict__ order, int m_total, int n_max, int n_pad, int hq,
     int hkv, int g, int nchunk, float c /* tau*log2(e) */, float eps, float *__restrict__ scores) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    float2 *mbox = reinterpret_cast<float2 *>(smem + kSearchBufs * kSearchTile);
     float2 *ms_all = reinterpret_cast<float2 *>(smem + kSearchStageBytes);
 
     const int per_row = hkv * nchunk;
@@ -75,120 +144,109 @@ __global__ __launch_bounds__(256, 1) void search_kernel(
     const int r = order[rank];
     const BlockRec bi = blk[r];
     const int I = r - bi.z;
-    const int tid = threadIdx.x, w = tid >> 6, l = tid & 63;
-    const int hg = ch * 4 + w;
+    const int tid = threadIdx.x, l = tid & 63, half = l >> 5;
+    const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, held in a scalar register
+    const int hd = w >> 1, qh = w & 1;
+    const int hg = ch * kSearchHeads + hd;
     const bool active = hg < g;
     const int h = hk * g + (active ? hg : g - 1);
-    float2 *ms = ms_all + (size_t)w * n_pad;
+    float2 *ms = ms_all + (size_t)hd * n_pad;
 
-    // Query tile as A-fragments: qa[qt][ks] covers queries 32qt + l%32, dims 16ks + 8(l/32)..+7.
-    bf16x8 qa[4][8];
-    {
-        const int half = l >> 5;
+    // Query fragments: qa[qt][ks] covers queries 64qh + 32qt + l%32, dims 16ks + 8(l/32)..+7.
+    bf16x8 qa[2][8];
 #pragma unroll
-        for (int qt = 0; qt < 4; ++qt) {
-            int row = 32 * qt + (l & 31);
-            row = row < bi.y ? row : bi.y - 1;   // rows past a ragged end are masked below
-            const uint16_t *qp = Q + ((size_t)(bi.x + row) * hq + h) * kHeadDim + 8 * half;
+    for (int qt = 0; qt < 2; ++qt) {
+        int row = 64 * qh + 32 * qt + (l & 31);
+        row = row < bi.y ? row : bi.y - 1;   // rows past a ragged end are masked in the reduction
+        const uint16_t *qp = Q + ((size_t)(bi.x + row) * hq + h) * kHeadDim + 8 * half;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) qa[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
-        }
+        for (int ks = 0; ks < 8; ++ks) qa[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
     }
 
+    // Tile loads: 16 wave-wide instructions per tile (2 planes x 8 groups of 4 rows), 4 per wave.
+    // Instruction q = 4w + i covers plane q/8, rows 4(q%8) + l/16; lane l fills LDS position l%16
+    // of its row, i.e. fetches global chunk (l%16) ^ (row & 15).  Rows past the diagonal
+    // (J > I) are clamped to I: they are computed and dropped.
     const int ntile = I / 32 + 1;
-    u32x4 sg0, sg1, sg2, sg3;
-    // Stage loader: 1024 16-byte chunks per tile (2 planes x 32 rows x 16 chunks), 4 per thread:
-    // thread -> (plane = i/2, row = tid/16 + 16*(i%2), col = tid%16) for i = 0..3
-    const int st_row = tid >> 4, st_col = tid & 15;
-#define FP_LOAD_ROW(i_, sg_)                                                                              \
-    {                                                                                                     \
-        int J_ = jbase_ + 16 * ((i_) & 1);                                                                \
-        J_ = J_ <= I ? J_ : I; /* columns past the diagonal are computed and dropped */                   \
-        sg_ = *reinterpret_cast<const u32x4 *>((((i_) >> 1) ? kb_lo : kb_hi) +                            \
-                                               ((size_t)(bi.z + J_) * hkv + hk) * kHeadDim + st_col * 8); \
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(FP_LDS(char) *)smem;
+    const uint32_t row_bytes = (uint32_t)hkv * kHeadDim * 2;
+    const char *pl_base = reinterpret_cast<const char *>(w < 2 ? kb_hi : kb_lo) + ((size_t)bi.z * hkv + hk) * kHeadDim * 2;
+    int ld_row[4];
+    uint32_t ld_col[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        ld_row[i] = 4 * ((4 * w + i) & 7) + (l >> 4);
+        ld_col[i] = (uint32_t)(((l & 15) ^ (ld_row[i] & 15)) * 16);
     }
 #define FP_LOAD_TILE(jt)                                                                                  \
     do {                                                                                                  \
-        const int jbase_ = 32 * (jt) + st_row;                                                            \
-        FP_LOAD_ROW(0, sg0) FP_LOAD_ROW(1, sg1) FP_LOAD_ROW(2, sg2) FP_LOAD_ROW(3, sg3)                   \
-    } while (0)
-#define FP_STORE_ROW(i_, sg_)                                                                             \
-    *reinterpret_cast<u32x4 *>(sd_ + ((i_) >> 1) * kSearchPlane + 16 * ((i_) & 1) * kSearchKbStride) = sg_;
-#define FP_STORE_TILE(buf)                                                                                \
-    do {                                                                                                  \
-        char *sd_ = smem + (buf) * kSearchStage + st_row * kSearchKbStride + st_col * 16;                 \
-        FP_STORE_ROW(0, sg0) FP_STORE_ROW(1, sg1) FP_STORE_ROW(2, sg2) FP_STORE_ROW(3, sg3)               \
+        const uint32_t dst_ = lds_base + (uint32_t)(((jt) % kSearchBufs) * kSearchTile) + (w >> 1) * kSearchPlane; \
+        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                \
+            int J_ = 32 * (jt) + ld_row[i_];                                                              \
+            J_ = J_ <= I ? J_ : I;                                                                        \
+            load_to_lds(pl_base, (uint32_t)J_ * row_bytes + ld_col[i_], dst_ + ((4 * w + i_) & 7) * 1024); \
+        }                                                                                                 \
     } while (0)
 
+    // B-fragment address inside a buffer: row l%32, chunk (2ks + half) ^ (row & 15).
+    const int brow = l & 31;
+    const uint32_t b_frag =
+        (uint32_t)(brow * 256 + ((((brow >> 1) & 7) << 5) | ((half ^ (brow & 1)) << 4)));
+#define FP_BUF(jt) ((uint32_t)(((jt) % kSearchBufs) * kSearchTile))
+
+    // Prologue: tile 0 (and the older Q loads) landed.
     FP_LOAD_TILE(0);
-    // Pin the Q fragments: their loads must have landed before the tile loop, or the compiler
-    // leaves waits on vector-memory loads between the loop's MFMAs (which in steady state would
-    // wait for the pooled-key prefetch issued just before).
 #pragma unroll
-    for (int qt = 0; qt < 4; ++qt)
+    for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qa[qt][ks]));
-    FP_STORE_TILE(0);
-    if (ntile > 1) FP_LOAD_TILE(1);
+        for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qa[qt][ks]));   // Q has landed before the loop
+    FP_WAIT_VMCNT(0);
     __syncthreads();
 
-    const int frag_off = (l & 31) * kSearchKbStride + (l >> 5) * 16;
-    for (int jt = 0; jt < ntile; ++jt) {
-        const int cur = jt & 1;
-        if (jt + 1 < ntile) FP_STORE_TILE(cur ^ 1);
-        if (jt + 2 < ntile) FP_LOAD_TILE(jt + 2);
-        if (active) {
-            f32x16 acc[4];
-#pragma unroll
-            for (int qt = 0; qt < 4; ++qt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[qt][i] = 0.f;
-            const char *tile = smem + cur * kSearchStage + frag_off;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
-                const bf16x8 bh = *reinterpret_cast<const bf16x8 *>(tile + ks * 32);
-                const bf16x8 bl = *reinterpret_cast<const bf16x8 *>(tile + kSearchPlane + ks * 32);
-#pragma unroll
-                for (int qt = 0; qt < 4; ++qt) acc[qt] = mfma32(qa[qt][ks], bh, acc[qt]);
-#pragma unroll
-                for (int qt = 0; qt < 4; ++qt) acc[qt] = mfma32(qa[qt][ks], bl, acc[qt]);
-            }
-            if (bi.y < kBlock) {   // ragged last q-block: leave missing queries out of max and sum
-#pragma unroll
-                for (int qt = 0; qt < 4; ++qt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const int row = 32 * qt + 8 * (i >> 2) + 4 * (l >> 5) + (i & 3);
-                        if (row >= bi.y) acc[qt][i] = -INFINITY;
-                    }
-            }
-            float mx = max3(acc[0][0], acc[1][0], acc[2][0]);
-            mx = max3(mx, acc[3][0], acc[3][0]);
-#pragma unroll
-            for (int i = 1; i < 16; ++i) {
-                mx = max3(mx, acc[0][i], acc[1][i]);
-                mx = max3(mx, acc[2][i], acc[3][i]);
-            }
-            mx = fmaxf(mx, __shfl_xor(mx, 32));
-            const float mc = mx * c;
-            float sum = 0.f;
-#pragma unroll
-            for (int qt = 0; qt < 4; ++qt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) sum += fast_exp2(__builtin_fmaf(acc[qt][i], c, -mc));
-            sum += __shfl_xor(sum, 32);
-            const int J = 32 * jt + (l & 31);
-            if (l < 32 && J <= I) ms[J] = make_float2(mc, sum);
-        }
-        __syncthreads();
-    }
+    // Step jt: tile jt is complete in LDS.  Issue tile jt+1 into the other buffer (its readers,
+    // step jt-1's MFMAs, are behind the barrier), compute and reduce tile jt; the upper query half
+    // posts its (max, sum) in the mailbox, the lower half merges the previous tile's post with
+    // its own pair from the previous step and files the result; wait for tile jt+1.
+    float2 prev = make_float2(-INFINITY, 0.f);
+#define FP_STEP(RAGGED, jt)                                                                               \
+    do {                                                                                                  \
+        const int jt_ = (jt);                                                                             \
+        if (jt_ + 1 < ntile) FP_LOAD_TILE(jt_ + 1);                                                       \
+        if (active) {                                                                                     \
+            f32x16 acc_[2];                                                                               \
+            search_mma(smem, FP_BUF(jt_) + b_frag, qa, acc_);                                             \
+            const float2 v_ = search_reduce<RAGGED>(acc_, c, bi.y, 64 * qh, half);                        \
+            if (l < 32) {                                                                                 \
+                if (qh) {                                                                                 \
+                    mbox[((jt_ & 1) * kSearchHeads + hd) * 32 + l] = v_;                                             \
+                } else {                                                                                  \
+                    const int Jp_ = 32 * (jt_ - 1) + l;                                                   \
+                    if (jt_ > 0 && Jp_ <= I) ms[Jp_] = search_merge(prev, mbox[(((jt_ - 1) & 1) * kSearchHeads + hd) * 32 + l]); \
+                    prev = v_;                                                                            \
+                }                                                                                         \
+            }                                                                                             \
+        }                                                                                                 \
+        FP_WAIT_VMCNT(0);                                                                                 \
+        __syncthreads();                                                                                  \
+    } while (0)
 
+    if (bi.y < kBlock) {
+        for (int jt = 0; jt < ntile; ++jt) FP_STEP(true, jt);
+    } else {
+        for (int jt = 0; jt < ntile; ++jt) FP_STEP(false, jt);
+    }
 #undef FP_LOAD_TILE
-#undef FP_STORE_TILE
-#undef FP_LOAD_ROW
-#undef FP_STORE_ROW
+#undef FP_BUF
+#undef FP_STEP
+    // the last tile's merge (its post is behind the loop's final barrier), then everyone meets once
+    // more so that both waves of a head see the complete (m, S) row
+    if (active && qh == 0 && l < 32) {
+        const int Jp = 32 * (ntile - 1) + l;
+        if (Jp <= I) ms[Jp] = search_merge(prev, mbox[(((ntile - 1) & 1) * kSearchHeads + hd) * 32 + l]);
+    }
+    __syncthreads();
     if (!active) return;
-    // Eq. 3-4: row max of the pair maxima, rescale, normalise, write the row once.
+    // Eq. 3-4: row max of the pair maxima, rescale, normalise; each wave writes half of the columns.
     float M = -INFINITY;
     for (int J = l; J <= I; J += 64) M = fmaxf(M, ms[J].x);
     M = wave_max(M);
@@ -200,7 +258,7 @@ __global__ __launch_bounds__(256, 1) void search_kernel(
     tot = wave_sum(tot);
     const float denom = tot + eps;
     float *out = scores + ((size_t)h * m_total + r) * n_max;
-    for (int J = l; J < n_max; J += 64) {
+    for (int J = l + 64 * qh; J < n_max; J += 128) {
         float p = 0.f;
         if (J <= I) {
             const float2 v = ms[J];
