@@ -151,6 +151,9 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
     ok = ok && hipMemcpy(p->d_order, order.data(), order.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize,
+                                   (int)(fp::kThresholdWaves * ((L.n_max + 63) / 64 * 64) * sizeof(float))) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<false>),
@@ -196,8 +199,10 @@ fp_status fp_threshold(fp_plan *p, const float *scores, const fp_params *params,
     const int sinkB = (params->sink_tokens + fp::kBlock - 1) / fp::kBlock;
     const int winB = (params->window_tokens + fp::kBlock - 1) / fp::kBlock;
     const int rows = p->hq * p->m_total;
-    fp::threshold_kernel<<<dim3((rows + 3) / 4), 256, 0, static_cast<hipStream_t>(hip_stream)>>>(
-        scores, p->d_blk, p->m_total, p->n_max, p->hq, params->alpha, sinkB, winB, idx, cnt);
+    const int n_pad = (p->n_max + 63) / 64 * 64;
+    fp::threshold_kernel<<<dim3((rows + fp::kThresholdWaves - 1) / fp::kThresholdWaves), 64 * fp::kThresholdWaves,
+                           (size_t)fp::kThresholdWaves * n_pad * sizeof(float), static_cast<hipStream_t>(hip_stream)>>>(
+        scores, p->d_blk, p->m_total, p->n_max, n_pad, p->hq, params->alpha, sinkB, winB, idx, cnt);
     return launch_status();
 }
 

@@ -269,25 +269,35 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
 }
 
 // ---------------------------------------------------------------------------------------------
-// Alg. 2.  One wave per (head, q-block row).  Pass 1: row max over J <= I with coalesced loads
-// and a wave reduction.  Pass 2: 64 candidates at a time, the keep decision
+// Alg. 2.  One wave per (head, q-block row).  Pass 1 reads the row's causal part once from HBM
+// with coalesced loads, keeps it in LDS and takes the row max with a wave reduction.  Pass 2
+// reads the row back from LDS, 64 candidates at a time: the keep decision
 // (score >= alpha*max, or sink, or window) becomes a ballot; the popcount of the lower lanes is
 // each kept block's slot, so the ascending list comes out without a sort or a scan over memory.
 // ---------------------------------------------------------------------------------------------
+constexpr int kThresholdWaves = 4;   // rows per workgroup
+
 __global__ __launch_bounds__(256) void threshold_kernel(const float *__restrict__ scores,
                                                         const BlockRec *__restrict__ blk, int m_total, int n_max,
-                                                        int hq, float alpha, int sinkB, int winB,
+                                                        int n_pad, int hq, float alpha, int sinkB, int winB,
                                                         int32_t *__restrict__ idx, int32_t *__restrict__ cnt) {
-    const int wave = blockIdx.x * 4 + (threadIdx.x >> 6);
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    const int wv = threadIdx.x >> 6;
+    const int wave = blockIdx.x * kThresholdWaves + wv;
     const int l = threadIdx.x & 63;
-    if (wave >= hq * m_total) return;
+    if (wave >= hq * m_total) return;   // no barrier in this kernel: waves are independent
+    float *buf = reinterpret_cast<float *>(smem) + (size_t)wv * n_pad;
     const int r = wave % m_total;   // wave = h*m_total + r
     const int I = r - blk[r].z;
     const float *row = scores + (size_t)wave * n_max;
     int32_t *out = idx + (size_t)wave * n_max;
 
     float mx = -INFINITY;
-    for (int J = l; J <= I; J += 64) mx = fmaxf(mx, row[J]);
+    for (int J = l; J <= I; J += 64) {
+        const float v = row[J];
+        buf[J] = v;
+        mx = fmaxf(mx, v);
+    }
     mx = wave_max(mx);
     const float thr = __fmul_rn(alpha, mx);   // one fp32 rounding, as the reference decision
 
@@ -295,7 +305,7 @@ __global__ __launch_bounds__(256) void threshold_kernel(const float *__restrict_
     for (int base = 0; base <= I; base += 64) {
         const int J = base + l;
         bool keep = false;
-        if (J <= I) keep = (row[J] >= thr) || (J < sinkB) || (I - J < winB);
+        if (J <= I) keep = (buf[J] >= thr) || (J < sinkB) || (I - J < winB);   // each lane re-reads what it wrote
         const unsigned long long bal = __ballot(keep);
         if (keep) out[count + __builtin_popcountll(bal & ((1ull << l) - 1ull))] = J;
         count += __builtin_popcountll(bal);
