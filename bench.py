@@ -30,6 +30,21 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+def profiled_traffic(workload_tag, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 --pmc summary for this workload
+    (FETCH_SIZE / WRITE_SIZE scaled by a known-size copy; see profiles/), or None."""
+    path = os.path.join(ROOT, "profiles", f"bench_{workload_tag}_hbm_bytes.txt")
+    try:
+        for line in open(path):
+            tok = line.split()
+            if tok and tok[0] == kernel and len(tok) >= 5:
+                rd, wr = float(tok[-2]) * 2**30, float(tok[-1]) * 2**30
+                return {"bytes": rd + wr, "read_bytes": rd, "write_bytes": wr, "source": os.path.relpath(path, ROOT)}
+    except OSError:
+        pass
+    return None
+
+
 def causal_pairs(row_offset, hq):
     n = np.diff(row_offset).astype(np.int64)
     return int((n * (n + 1) // 2).sum()) * hq
@@ -104,8 +119,40 @@ def run_workload(w, steps, warmup, dense_runs, torch, B):
         sparse_tflops=kept * PAIR_FLOPS / sparse_ms / 1e9,
         dense_tflops=(pairs * PAIR_FLOPS / dense_ms / 1e9) if dense_ms else None,
     )
-    host = dict(Q=Q, K=K, V=V, cu=cu, idx=idx, cnt=cnt, O=O, scores=scores, plan=plan)
+    host = dict(Q=Q, K=K, V=V, cu=cu, idx=idx, cnt=cnt, O=O, scores=scores, plan=plan, dQ=dQ, dK=dK, dV=dV)
     return res, host
+
+
+def forced_density_run(w, host, density, steps, torch):
+    """Sparse kernel alone on random causal lists (sink and window blocks always kept) of a target
+    density: the measurement shape of the paper's block-sparse latency table."""
+    plan = host["plan"]
+    hq, m, n = w.hq, plan.m_total, plan.n_max
+    idx, cnt = host["idx"], host["cnt"]
+    ro = plan.row_offset
+    I = torch.cat([torch.arange(int(ro[s + 1] - ro[s])) for s in range(len(ro) - 1)]).cuda()[:, None]
+    J = torch.arange(n, device="cuda")[None, :]
+    g = torch.Generator(device="cuda"); g.manual_seed(1234)
+    for h in range(hq):
+        keep = (torch.rand((m, n), device="cuda", generator=g) < density) | (J < 2) | ((I - J >= 0) & (I - J < 4))
+        keep &= J <= I
+        idx[h] = torch.sort((~keep).to(torch.uint8), dim=-1, stable=True).indices.int()
+        cnt[h] = keep.sum(-1).int()
+    kept = int(cnt.sum().item())
+    dQ, dK, dV = (host[k] for k in ("dQ", "dK", "dV"))
+    O = host["O"]
+    plan.fp_sparse_prefill(dQ, dK, dV, idx, cnt, O, want_lse=False)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        plan.fp_sparse_prefill(dQ, dK, dV, idx, cnt, O, want_lse=False)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    pairs = causal_pairs(plan.row_offset, hq)
+    return dict(target_density=density, density=kept / pairs, sparse_attention_ms=ms,
+                sparse_tflops=kept * PAIR_FLOPS / ms / 1e9)
 
 
 def cpu_baseline(w, host, res, torch, budget_pairs=16000):
@@ -167,6 +214,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=3, help="workload 0..4 (3 = Qwen3-30B-A3B shape, 256K tokens)")
     ap.add_argument("--no-supplementary", action="store_true", help="skip the block-coherent-planting run")
+    ap.add_argument("--planting", choices=["literal", "coherent"], default="literal",
+                    help="input recipe of the headline workload (coherent: the block-coherent planting only)")
+    ap.add_argument("--forced-density", type=float, nargs="*", default=[],
+                    help="also time the sparse kernel alone on random causal lists of these densities")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
@@ -186,7 +237,9 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
-    w = synth.config(a.config, "literal")
+    w = synth.config(a.config, a.planting)
+    if a.planting == "coherent":
+        a.no_supplementary = True
     res, host = run_workload(w, a.steps, a.warmup, dense_runs=2, torch=torch, B=B)
     log(f"[bench] {json.dumps(res)}")
     cpu = None
@@ -195,6 +248,10 @@ def main():
         cpu = cpu_baseline(w, host, res, torch)
         log(f"[bench] cpu_baseline {json.dumps(cpu)}")
     dense_ms = res["ms"]["dense"]
+    forced = []
+    for dens in a.forced_density:
+        forced.append(forced_density_run(w, host, dens, a.steps, torch))
+        log(f"[bench] forced density {json.dumps(forced[-1])}")
     del host
     torch.cuda.empty_cache()
 
@@ -223,19 +280,25 @@ def main():
         "ms_per_step": e2e, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"{w.name}: B=1 Hq={w.hq} Hkv={w.hkv} d=128 S={w.total_tokens} causal bf16, "
-                               f"block 128, alpha={w.alpha}, sink 256, window 512, generator as configured "
-                               f"(N(0,1), RoPE 1e6, {w.n_vert} single-token vertical plants, {w.n_slash} slash lags)"},
+                               f"block 128, alpha={w.alpha}, sink 256, window 512, "
+                               + ("generator as configured (N(0,1), RoPE 1e6, "
+                                  f"{w.n_vert} single-token vertical plants, {w.n_slash} slash lags)" if w.mode == "literal"
+                                  else "block-coherent planting (supplementary recipe, see DESIGN.md)")},
         "stages_ms": res["ms"], "density": res["density"], "speedup_vs_own_dense": res["speedup_vs_own_dense"],
         "roofline": {"bound": "mfma", "kernel": "attn_kernel<sparse>", "achieved": res["sparse_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": res["sparse_tflops"] / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": None},
+                     "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, "fp::attn_kernel<true>") or {}).get("bytes"),
+                     "traffic_detail": profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, "fp::attn_kernel<true>")},
         "roofline_search": {"bound": "hbm", "kernel": "pool_k_kernel+search_kernel", "achieved": res["search_gbs"],
                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["search_gbs"] / HBM_PEAK_GBS,
-                            "mfma_tflops_two_pass": res["search_mfma_tflops"], "traffic": None},
+                            "mfma_tflops_two_pass": res["search_mfma_tflops"],
+                            "mfma_frac_two_pass": res["search_mfma_tflops"] / MFMA_BF16_PEAK_TFLOPS,
+                            "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, "fp::search_kernel") or {}).get("bytes")},
         "roofline_dense": {"bound": "mfma", "kernel": "attn_kernel<dense>", "achieved": res["dense_tflops"],
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": (res["dense_tflops"] or 0) / MFMA_BF16_PEAK_TFLOPS},
         "cpu_baseline": cpu,
+        "forced_density": forced or None,
         "supplementary_block_coherent_planting": sup,
         "paper_context": "paper reports 27.78x at 256K and 1.71x at 4K vs FlashAttention 2.8.3 on NVIDIA H20 (real activations, density 3.5% at 256K)",
     }
