@@ -57,6 +57,7 @@ struct fp_plan {
     float c = 0.f;                    // tau * log2(e)
     fp::BlockRec *d_blk = nullptr;    // [m_total]
     int32_t *d_order = nullptr;       // [m_total] rows, largest I first
+    fp::BlockRec *d_blk_ranked = nullptr;   // [m_total] d_blk permuted by d_order
     uint16_t *d_kb_hi = nullptr;      // [m_total, hkv, 128] bf16
     uint16_t *d_kb_lo = nullptr;
     size_t search_lds = 0;
@@ -93,6 +94,7 @@ void fp_plan_destroy(fp_plan *p) {
     if (hipSetDevice(p->device) == hipSuccess) {
         if (p->d_blk) (void)hipFree(p->d_blk);
         if (p->d_order) (void)hipFree(p->d_order);
+        if (p->d_blk_ranked) (void)hipFree(p->d_blk_ranked);
         if (p->d_kb_hi) (void)hipFree(p->d_kb_hi);
         if (p->d_kb_lo) (void)hipFree(p->d_kb_lo);
     }
@@ -139,16 +141,21 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
     std::stable_sort(order.begin(), order.end(),
                      [&](int32_t x, int32_t y) { return x - blk[(size_t)x].z > y - blk[(size_t)y].z; });
 
+    std::vector<fp::BlockRec> blk_ranked((size_t)L.m_total);
+    for (int i = 0; i < L.m_total; ++i) blk_ranked[(size_t)i] = blk[(size_t)order[(size_t)i]];
+
     int prev = 0;
     (void)hipGetDevice(&prev);
     bool ok = hipSetDevice(device) == hipSuccess;
     const size_t kb_bytes = (size_t)L.m_total * p->hkv * fp::kHeadDim * sizeof(uint16_t);
     ok = ok && hipMalloc(&p->d_blk, blk.size() * sizeof(fp::BlockRec)) == hipSuccess;
     ok = ok && hipMalloc(&p->d_order, order.size() * sizeof(int32_t)) == hipSuccess;
+    ok = ok && hipMalloc(&p->d_blk_ranked, blk.size() * sizeof(fp::BlockRec)) == hipSuccess;
     ok = ok && hipMalloc(&p->d_kb_hi, kb_bytes) == hipSuccess;
     ok = ok && hipMalloc(&p->d_kb_lo, kb_bytes) == hipSuccess;
     ok = ok && hipMemcpy(p->d_blk, blk.data(), blk.size() * sizeof(fp::BlockRec), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_order, order.data(), order.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(p->d_blk_ranked, blk_ranked.data(), blk.size() * sizeof(fp::BlockRec), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel),
@@ -184,7 +191,7 @@ fp_status fp_block_search(fp_plan *p, const void *Q, const void *K, float eps, f
                                                                  p->d_kb_hi, p->d_kb_lo);
     const int nchunk = (p->g + fp::kSearchHeads - 1) / fp::kSearchHeads;
     fp::search_kernel<<<dim3(p->m_total * p->hkv * nchunk), 256, p->search_lds, st>>>(
-        static_cast<const uint16_t *>(Q), p->d_kb_hi, p->d_kb_lo, p->d_blk, p->d_order, p->m_total, p->n_max, p->n_pad,
+        static_cast<const uint16_t *>(Q), p->d_kb_hi, p->d_kb_lo, p->d_blk_ranked, p->d_order, p->m_total, p->n_max, p->n_pad,
         p->hq, p->hkv, p->g, nchunk, p->c, eps, scores);
     return launch_status();
 }
@@ -216,10 +223,10 @@ static fp_status launch_attn(fp_plan *p, bool sparse, const void *Q, const void 
                    *v = static_cast<const uint16_t *>(V);
     uint16_t *o = static_cast<uint16_t *>(O);
     if (sparse)
-        fp::attn_kernel<true><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, idx, cnt, p->d_blk, p->d_order, p->m_total, p->n_max,
+        fp::attn_kernel<true><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, idx, cnt, p->d_blk_ranked, p->d_order, p->m_total, p->n_max,
                                                            p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     else
-        fp::attn_kernel<false><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, nullptr, nullptr, p->d_blk, p->d_order, p->m_total,
+        fp::attn_kernel<false><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, nullptr, nullptr, p->d_blk_ranked, p->d_order, p->m_total,
                                                             p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     return launch_status();
 }

@@ -157,7 +157,7 @@ __device__ __forceinline__ void attn_pv(const char *smem, const uint32_t (&vaddr
 template <bool SPARSE>
 __global__ __launch_bounds__(256, 2) void attn_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
-    const int32_t *__restrict__ idx, const int32_t *__restrict__ cnt, const BlockRec *__restrict__ blk,
+    const int32_t *__restrict__ idx, const int32_t *__restrict__ cnt, const BlockRec *__restrict__ blk_ranked,
     const int32_t *__restrict__ order, int m_total, int n_max, int hq, int hkv, int g, int T, float c,
     uint16_t *__restrict__ O, float *__restrict__ lse) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -166,9 +166,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     const int s = (k / g) * 8 + x, hg = k % g;
     if (s >= m_total * hkv) return;
     const int rank = s / hkv, hk = s - rank * hkv;
-    const int r = order[rank];
+    const int r = order[rank];               // both tables are indexed by rank: one round trip
+    const BlockRec bi = blk_ranked[rank];
     const int h = hk * g + hg;
-    const BlockRec bi = blk[r];
     const int I = r - bi.z;
     const int seq_tok0 = bi.x - I * kBlock;
     const int last_tok = bi.w - 1;
@@ -177,13 +177,19 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, held in a scalar register
     const int q_local = 32 * w + (l & 31);
 
-    int nb = I + 1;
+    // The first two list entries are fetched together with the count (the memory is there whatever
+    // the count says), so that the first tile loads do not wait for a second round trip.
+    int nb = I + 1, b0 = 0, b1 = 1;
     const int32_t *list = nullptr;
     if (SPARSE) {
         list = idx + ((size_t)h * m_total + r) * n_max;
         nb = cnt[(size_t)h * m_total + r];
+        b0 = list[0];
+        b1 = list[n_max > 1 ? 1 : 0];
         nb = nb < 0 ? 0 : (nb > I + 1 ? I + 1 : nb);
     }
+    b0 = b0 < 0 ? 0 : (b0 > I ? I : b0);
+    b1 = b1 < 0 ? 0 : (b1 > I ? I : b1);
     const int ntiles = 2 * nb;
 
     if (ntiles == 0) {   // empty list: O = 0, lse = -inf (uniform exit, before any barrier)
@@ -227,16 +233,15 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
         ld_kcol[i] = (uint32_t)((ld_pos ^ (row & 15)) * 16);
         ld_vcol[i] = (uint32_t)((ld_pos ^ (4 * (row & 3))) * 16);
     }
-#define FP_LOAD(FULL, Xb, col_, t, ldsoff_)                                                               \
+#define FP_LOAD(FULL, Xb, col_, blk_, odd_, ldsoff_)                                                      \
     do {                                                                                                  \
-        const int tok0_ = seq_tok0 + FP_TILE_BLOCK(t) * kBlock + ((t) & 1) * kAttnTileKeys;               \
-        const bool ragged_ = !(FULL) && tok0_ + kAttnTileKeys - 1 > last_tok;                             \
+        const int tok0_ = seq_tok0 + (blk_) * kBlock + (odd_) * kAttnTileKeys;                            \
         const int base_tok_ = tok0_ < last_tok ? tok0_ : last_tok;                                        \
         const char *base_ = Xb + (size_t)base_tok_ * row_bytes;                                           \
         const uint32_t dst_ = lds_base + (ldsoff_) + 16 * w * kAttnRowBytes;                              \
         _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                \
             uint32_t ro_ = (uint32_t)(ld_row + 4 * i_) * row_bytes;                                       \
-            if (ragged_) {                                                                                \
+            if (!(FULL)) {                                                                                \
                 int tok_ = tok0_ + ld_row + 4 * i_;                                                       \
                 tok_ = tok_ < last_tok ? tok_ : last_tok; /* keys past the end are masked as future */    \
                 ro_ = (uint32_t)(tok_ - base_tok_) * row_bytes; /* tok_ >= base_tok_ */                   \
@@ -244,12 +249,23 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
             load_to_lds(base_, ro_ + col_[i_], dst_ + 4 * i_ * kAttnRowBytes);                            \
         }                                                                                                 \
     } while (0)
-    // FULL: the tile is known to lie in a block before the diagonal one, hence complete.
     // K tile t lives in K buffer t % 3, V tile t in V buffer t % 2.
 #define FP_KBUF(t) ((uint32_t)(((t) % kAttnKBufs) * kAttnTile))
 #define FP_VBUF(t) ((uint32_t)(kAttnVBase + ((t) & 1) * kAttnTile))
-#define FP_LOAD_K(FULL, t) FP_LOAD(FULL, Kb, ld_kcol, t, FP_KBUF(t))
-#define FP_LOAD_V(FULL, t) FP_LOAD(FULL, Vb, ld_vcol, t, FP_VBUF(t))
+    // FULL loads are for tiles known to lie before the diagonal block, hence complete; the block id
+    // is kept below I so that even a malformed (non-ascending) list cannot reach past the sequence.
+    // Other loads clamp every row to the sequence's last token, and the tile index to the row's
+    // last tile: a prefetch past the end of the list re-reads that tile into a buffer nobody reads.
+#define FP_LOAD_FULL(Xb, col_, t, ldsoff_)                                                                \
+    do {                                                                                                  \
+        const int b_ = FP_TILE_BLOCK(t);                                                                  \
+        FP_LOAD(true, Xb, col_, (b_ < I ? b_ : I - 1), ((t) & 1), ldsoff_);                               \
+    } while (0)
+#define FP_LOAD_SAFE(Xb, col_, t, ldsoff_)                                                                \
+    do {                                                                                                  \
+        const int ts_ = (t) < ntiles ? (t) : ntiles - 1;                                                  \
+        FP_LOAD(false, Xb, col_, FP_TILE_BLOCK(ts_), (ts_ & 1), ldsoff_);                                 \
+    } while (0)
 
     f32x16 acc[4];
 #pragma unroll
@@ -272,84 +288,97 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt) v_frag[dt] = vb + (uint32_t)((dt ^ e) * 64);
     }
-    // A tile of the diagonal block that lies wholly in this wave's future is skipped.
-#define FP_SKIP(t) (FP_TILE_BLOCK(t) == I && ((t) & 1) * kAttnTileKeys > 32 * w + 31)
+    // Causal limit of tile t for this lane: on the diagonal block, key kk of the tile is in the
+    // lane's future if kk > query - tile offset (and keys past a ragged end lie beyond every stored
+    // query); elsewhere nothing is masked.
+#define FP_LIM(t) (FP_TILE_BLOCK(t) == I ? q_local - ((t) & 1) * kAttnTileKeys - 4 * half : 2 * kAttnTileKeys)
 
     // Prologue: K[0], V[0], K[1] landed, K[2] on its way; S^T of tile 0 with its row max.
-    FP_LOAD_K(false, 0);
-    FP_LOAD_V(false, 0);
+    FP_LOAD(false, Kb, ld_kcol, b0, 0, FP_KBUF(0));
+    FP_LOAD(false, Vb, ld_vcol, b0, 0, FP_VBUF(0));
     // Pin the Q fragments: their loads are issued by now and are older than everything the loop
     // waits for, so no wait on them can end up between the loop's MFMAs.
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[ks]));
-    if (ntiles > 1) FP_LOAD_K(false, 1);
-    if (ntiles > 2) {
-        FP_LOAD_K(false, 2);
-        FP_WAIT_VMCNT(4);
-    } else {
-        FP_WAIT_VMCNT(0);
-    }
+    FP_LOAD(false, Kb, ld_kcol, b0, 1, FP_KBUF(1));   // ntiles >= 2
+    FP_LOAD(false, Kb, ld_kcol, (nb > 1 ? b1 : b0), (nb > 1 ? 0 : 1), FP_KBUF(2));
+    FP_WAIT_VMCNT(4);
     __syncthreads();
     f32x16 sA0, sA1, sB0, sB1;
-    attn_qk(smem, FP_KBUF(0) + k_frag, qb, sA0, sA1);   // tile 0 is never skipped (it starts at or before every query)
-    if (FP_TILE_BLOCK(0) == I) attn_mask(sA0, sA1, q_local - 4 * half);
-    m_run = attn_rowmax(sA0, sA1);                      // finite: key 0 of tile 0 is visible to every query
+    attn_qk(smem, FP_KBUF(0) + k_frag, qb, sA0, sA1);
+    attn_mask(sA0, sA1, b0 == I ? q_local - 4 * half : 2 * kAttnTileKeys);
+    m_run = attn_rowmax(sA0, sA1);   // finite: key 0 of tile 0 is visible to every query
 
     // Step t.  On entry K[t+1] and V[t] are complete in LDS, K[t+2] may still be landing, S^T(t) is
     // in (c0, c1) and its row max is already folded into m_run (accumulator rescaled).  The step
     // issues V[t+1] into the buffer V[t-1] used and K[t+3] into the buffer K[t] used (all waves are
     // past step t-1's barrier, which was their last reader) and ends by waiting for everything but
-    // K[t+3].  PLAIN steps carry no guard at all (tiles t .. t+3 lie before the diagonal block, so
-    // every prefetch exists and is a complete tile): the step is one basic block and the scheduler
-    // can interleave the QK^T MFMAs of tile t+1 with the exponentials of tile t, and the PV MFMAs
-    // of tile t with the max of t+1.
-#define FP_STEP(PLAIN, t, c0, c1, n0, n1)                                                                 \
+    // K[t+3].  Every variant is straight-line code, so that the scheduler can interleave the QK^T
+    // MFMAs of tile t+1 with the exponentials of tile t, and the PV MFMAs of tile t with the max of
+    // tile t+1:
+    //   MAIN  tiles t .. t+3 lie before the diagonal block: cheap loads, no mask;
+    //   TAIL  row-clamped loads and the (branch-free) causal limit of tile t+1;
+    //   PEN   the last but one step: as TAIL without a K prefetch, ends with nothing in flight;
+    //   LAST  exponentials and PV of the last tile only.
+    // A tile of the diagonal block that lies wholly in a wave's future needs no special case: its
+    // logits are all -inf, which leaves the max alone and contributes zeros.
+    enum { MAIN = 0, TAIL = 1, PEN = 2, LAST = 3 };
+#define FP_STEP(MODE, t, c0, c1, n0, n1)                                                                  \
     do {                                                                                                  \
         const int t_ = (t);                                                                               \
-        const bool more_ = PLAIN || t_ + 3 < ntiles;                                                      \
-        if (PLAIN || t_ + 1 < ntiles) FP_LOAD_V(PLAIN, t_ + 1);                                           \
-        if (more_) FP_LOAD_K(PLAIN, t_ + 3);                                                              \
-        const bool do_cur_ = PLAIN || !FP_SKIP(t_);                                                       \
-        const bool do_nxt_ = PLAIN || (t_ + 1 < ntiles && !FP_SKIP(t_ + 1));                              \
+        if (MODE == MAIN) {                                                                               \
+            FP_LOAD_FULL(Vb, ld_vcol, t_ + 1, FP_VBUF(t_ + 1));                                           \
+            FP_LOAD_FULL(Kb, ld_kcol, t_ + 3, FP_KBUF(t_ + 3));                                           \
+        } else if (MODE != LAST) {                                                                        \
+            FP_LOAD_SAFE(Vb, ld_vcol, t_ + 1, FP_VBUF(t_ + 1));                                           \
+            if (MODE == TAIL) FP_LOAD_SAFE(Kb, ld_kcol, t_ + 3, FP_KBUF(t_ + 3));                         \
+        }                                                                                                 \
         bf16x8 pb_[2][2];                                                                                 \
-        if (do_cur_) attn_exp(c0, c1, c, m_run * c, l_run, pb_);                                          \
-        if (do_nxt_) attn_qk(smem, FP_KBUF(t_ + 1) + k_frag, qb, n0, n1);                                 \
-        if (do_cur_) {                                                                                    \
+        attn_exp(c0, c1, c, m_run * c, l_run, pb_);                                                       \
+        if (MODE != LAST) attn_qk(smem, FP_KBUF(t_ + 1) + k_frag, qb, n0, n1);                            \
+        {                                                                                                 \
             uint32_t va_[4];                                                                              \
             _Pragma("unroll") for (int dt_ = 0; dt_ < 4; ++dt_) va_[dt_] = FP_VBUF(t_) + v_frag[dt_];     \
             attn_pv(smem, va_, pb_, acc);                                                                 \
         }                                                                                                 \
-        if (do_nxt_) {                                                                                    \
-            if (!PLAIN && FP_TILE_BLOCK(t_ + 1) == I)                                                     \
-                attn_mask(n0, n1, q_local - ((t_ + 1) & 1) * kAttnTileKeys - 4 * half);                   \
+        if (MODE != LAST) {                                                                               \
+            if (MODE != MAIN) attn_mask(n0, n1, FP_LIM(t_ + 1));                                          \
             attn_new_max(attn_rowmax(n0, n1), c, m_run, l_run, acc);                                      \
+            if (MODE == PEN) FP_WAIT_VMCNT(0);                                                            \
+            else FP_WAIT_VMCNT(4);                                                                        \
+            __syncthreads();                                                                              \
         }                                                                                                 \
-        if (more_) FP_WAIT_VMCNT(4);                                                                      \
-        else FP_WAIT_VMCNT(0);                                                                            \
-        __syncthreads();                                                                                  \
     } while (0)
 
-    // Tiles before the diagonal block are plain (and complete: only a sequence's last block can be
-    // partial, and a row only meets it as its diagonal); the list is ascending, so only its last
-    // block can be the diagonal one.  A plain step t needs tiles t .. t+3 plain.
+    // Tiles before the diagonal block are complete (only a sequence's last block can be partial,
+    // and a row only meets it as its diagonal); the list is ascending, so only its last block can
+    // be the diagonal one.  A MAIN step t needs tiles t .. t+3 before it.  ntiles is even, and so
+    // is the number of MAIN steps, so the register roles of the two S^T tiles alternate evenly.
     const int n_plain = FP_TILE_BLOCK(ntiles - 1) == I ? ntiles - 2 : ntiles;
-    const int t_main = (n_plain - 3) & ~1;   // even count of plain steps (negative: none)
+    const int t_main = (n_plain - 3) & ~1;   // negative: none
     int t = 0;
     for (; t < t_main; t += 2) {
-        FP_STEP(true, t, sA0, sA1, sB0, sB1);
-        FP_STEP(true, t + 1, sB0, sB1, sA0, sA1);
+        FP_STEP(MAIN, t, sA0, sA1, sB0, sB1);
+        FP_STEP(MAIN, t + 1, sB0, sB1, sA0, sA1);
     }
-    for (; t < ntiles; t += 2) {
-        FP_STEP(false, t, sA0, sA1, sB0, sB1);
-        if (t + 1 >= ntiles) break;
-        FP_STEP(false, t + 1, sB0, sB1, sA0, sA1);
+    for (; t < ntiles - 2; t += 2) {
+        FP_STEP(TAIL, t, sA0, sA1, sB0, sB1);
+        FP_STEP(TAIL, t + 1, sB0, sB1, sA0, sA1);
     }
+    FP_STEP(PEN, t, sA0, sA1, sB0, sB1);
+    FP_STEP(LAST, t + 1, sB0, sB1, sA0, sA1);
 
     // O = acc / l, lse = m + log2 l (Alg. 3, final normalisation); rows past a ragged end are not stored.
+    // Each lane holds 4 consecutive dims of one query per accumulator group, which would make every
+    // global store touch 64 different rows.  The wave's 32 x 128 output tile is therefore turned
+    // through LDS (its own 8 KB of the K buffers: their last reader and their last incoming load
+    // finished before the barrier of the last-but-one step) into 16-byte pieces, 16 lanes per row.
+    // Chunk c of row q is kept at chunk c ^ (q & 15) so that neither side meets a bank conflict.
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    if (q_local < bi.y) {
-        uint16_t *op = O + ((size_t)(bi.x + q_local) * hq + h) * kHeadDim + 4 * half;
+    {
+        char *ob = smem + w * (32 * kAttnRowBytes);
+        const int qrow = l & 31;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
@@ -357,18 +386,29 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
                 bf16x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = (__bf16)(acc[dt][4 * q4 + e] * inv);
-                *reinterpret_cast<bf16x4 *>(op + 32 * dt + 8 * q4) = o;
+                *reinterpret_cast<bf16x4 *>(ob + qrow * kAttnRowBytes + (((4 * dt + q4) ^ (qrow & 15)) << 4) + 8 * half) = o;
             }
-        if (lse != nullptr && half == 0)
-            lse[(size_t)h * T + bi.x + q_local] = l_tot > 0.f ? m_run * c + __log2f(l_tot) : -INFINITY;
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const int pc = l & 15;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int orow = 4 * i + (l >> 4);
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(ob + orow * kAttnRowBytes + (pc << 4));
+            if (32 * w + orow < bi.y)
+                *reinterpret_cast<u32x4 *>(O + ((size_t)(bi.x + 32 * w + orow) * hq + h) * kHeadDim + ((pc ^ (orow & 15)) << 3)) = v;
+        }
     }
+    if (q_local < bi.y && lse != nullptr && half == 0)
+        lse[(size_t)h * T + bi.x + q_local] = l_tot > 0.f ? m_run * c + __log2f(l_tot) : -INFINITY;
 #undef FP_TILE_BLOCK
 #undef FP_LOAD
-#undef FP_LOAD_K
-#undef FP_LOAD_V
+#undef FP_LOAD_FULL
+#undef FP_LOAD_SAFE
+#undef FP_LIM
 #undef FP_KBUF
 #undef FP_VBUF
-#undef FP_SKIP
 #undef FP_STEP
 }
 

@@ -131,8 +131,8 @@ __device__ __forceinline__ float2 search_merge(float2 a, float2 b) {
 
 __global__ __launch_bounds__(256, 4) void search_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ kb_hi, const uint16_t *__restrict__ kb_lo,
-    const BlockRec *__restrict__ blk, const int32_t *__restrict__ order, int m_total, int n_max, int n_pad, int hq,
-    int hkv, int g, int nchunk, float c /* tau*log2(e) */, float eps, float *__restrict__ scores) {
+    const BlockRec *__restrict__ blk_ranked, const int32_t *__restrict__ order, int m_total, int n_max, int n_pad,
+    int hq, int hkv, int g, int nchunk, float c /* tau*log2(e) */, float eps, float *__restrict__ scores) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     float2 *mbox = reinterpret_cast<float2 *>(smem + kSearchBufs * kSearchTile);
     float2 *ms_all = reinterpret_cast<float2 *>(smem + kSearchStageBytes);
@@ -142,7 +142,7 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     const int rem = blockIdx.x - rank * per_row;
     const int hk = rem / nchunk, ch = rem - hk * nchunk;
     const int r = order[rank];
-    const BlockRec bi = blk[r];
+    const BlockRec bi = blk_ranked[rank];
     const int I = r - bi.z;
     const int tid = threadIdx.x, l = tid & 63, half = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, held in a scalar register
