@@ -103,6 +103,18 @@ def run_workload(w, steps, warmup, dense_runs, torch, B):
         dense_ms = e0.elapsed_time(e1) / dense_runs
         del Od
 
+    # the one-pass search + selection entry point (same lists, no score matrix), timed on its own
+    plan.fp_search_select(dQ, dK, w.alpha, idx=idx, cnt=cnt)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        plan.fp_search_select(dQ, dK, w.alpha, idx=idx, cnt=cnt)
+    e1.record()
+    torch.cuda.synchronize()
+    fused_ms = e0.elapsed_time(e1) / steps
+    assert int(cnt.sum().item()) == kept
+
     T = plan.T
     search_bytes = 2 * T * 128 * (w.hq + w.hkv) + 4 * pairs          # Q once + K once + one fp32 per causal pair
     thr_bytes = 4 * pairs + 4 * kept + 4 * hq * m
@@ -110,9 +122,10 @@ def run_workload(w, steps, warmup, dense_runs, torch, B):
         workload=w.name, tokens=T, hq=w.hq, hkv=w.hkv, alpha=w.alpha, planting=w.mode,
         ms=dict(search=float(search_ms), threshold=float(thr_ms), sparse_attention=float(sparse_ms),
                 end_to_end=float(search_ms + thr_ms + sparse_ms), end_to_end_wall=float(wall_ms),
-                dense=dense_ms),
+                search_select_fused=float(fused_ms), end_to_end_fused=float(fused_ms + sparse_ms), dense=dense_ms),
         density=kept / pairs, kept_pairs=kept, causal_pairs=pairs,
         speedup_vs_own_dense=(dense_ms / float(search_ms + thr_ms + sparse_ms)) if dense_ms else None,
+        speedup_vs_own_dense_fused=(dense_ms / float(fused_ms + sparse_ms)) if dense_ms else None,
         search_gbs=search_bytes / search_ms / 1e6,
         search_mfma_tflops=pairs * 2 * 128 * 128 * 2 / search_ms / 1e9,   # two bf16 passes (hi, lo) per pair
         threshold_gbs=thr_bytes / thr_ms / 1e6,
@@ -220,7 +233,7 @@ def main():
                     help="also time the sparse kernel alone on random causal lists of these densities")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--sweep", action="store_true",
-                    help="length sweep 4K..256K on the Qwen3-30B-A3B shape (block-coherent planting): per-stage ms, "
+                    help="length sweep 4K..512K on the Qwen3-30B-A3B shape (block-coherent planting): per-stage ms, "
                          "speedup over the own dense kernel, and the sparse kernel alone at forced 60 %% / 6 %% density")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
@@ -243,7 +256,7 @@ def main():
     if a.sweep:
         import dataclasses
         rows = []
-        for L in (4096, 8192, 16384, 32768, 65536, 131072, 262144):
+        for L in (4096, 8192, 16384, 32768, 65536, 131072, 262144, 524288):
             wl = dataclasses.replace(synth.config(1, "coherent"), seqlens=(L,), name=f"qwen3_shape_{L // 1024}k_coherent")
             r, h = run_workload(wl, a.steps, a.warmup, dense_runs=2, torch=torch, B=B)
             r["forced_density"] = [forced_density_run(wl, h, d, a.steps, torch) for d in (0.6, 0.06)]
@@ -254,7 +267,7 @@ def main():
         print(json.dumps({"metric": "sparse prefill ms/layer vs length (sweep)", "unit": "ms/layer", "n_gpus": 1,
                           "steps": a.steps, "warmup": a.warmup, "dtype": "bf16", "data": "synthetic",
                           "config": {"workload": "Qwen3-30B-A3B attention shape (Hq=32, Hkv=4, d=128), block-coherent planting, "
-                                                 "alpha=0.12, 4K..256K tokens"},
+                                                 "alpha=0.12, 4K..512K tokens"},
                           "paper_context": "paper (NVIDIA H20, real activations): speedup vs FlashAttention 1.71/2.79/4.48/6.94/11.45/18.67/27.78x "
                                            "at 4K..256K; densities 70.4/46.0/29.0/17.6/10.0/5.8/3.5 %",
                           "sweep": rows}), flush=True)
@@ -316,7 +329,7 @@ def main():
                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["search_gbs"] / HBM_PEAK_GBS,
                             "mfma_tflops_two_pass": res["search_mfma_tflops"],
                             "mfma_frac_two_pass": res["search_mfma_tflops"] / MFMA_BF16_PEAK_TFLOPS,
-                            "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, "fp::search_kernel") or {}).get("bytes")},
+                            "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, "fp::search_kernel<false>") or {}).get("bytes")},
         "roofline_dense": {"bound": "mfma", "kernel": "attn_kernel<dense>", "achieved": res["dense_tflops"],
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": (res["dense_tflops"] or 0) / MFMA_BF16_PEAK_TFLOPS},

@@ -100,6 +100,17 @@ fp_status fp_threshold(fp_plan *plan, const float *scores, const fp_params *para
                        void *hip_stream);
 
 /*
+ * Stages (i) + (ii) in one pass: the lists fp_threshold would emit from fp_block_search's scores,
+ * without the scores ever reaching memory.  Each row's normalised scores are formed in on-chip
+ * memory with the same fp32 arithmetic and compared with alpha * their max there, so idx and cnt
+ * are identical to those of the two calls in a row (Alg. 1 stage 3 feeding Alg. 2; the paper's
+ * Appendix B keeps the two apart, this entry point is the shortcut its Sec. 3.4 decision rule
+ * allows because the rule only looks at one row at a time).  Arguments as in the two calls.
+ */
+fp_status fp_search_select(fp_plan *plan, const void *Q, const void *K, float eps, const fp_params *params,
+                           int32_t *idx, int32_t *cnt, void *hip_stream);
+
+/*
  * Stage (iii).  Alg. 3: for each (head, q-block row) visit only the listed key blocks, online
  * softmax in base 2, causal mask on the diagonal block only; O = acc / l, lse = m + log2 l
  * (base-2 log-sum-exp of tau*log2(e)*q.k over the visited, non-future keys).  `lse` may be

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libflashprefill.so")
 FP_OK, FP_ERR_INVALID_ARG, FP_ERR_UNSUPPORTED, FP_ERR_DEVICE, FP_ERR_NOMEM = range(5)
 
 EXPORTS = ("fp_status_string", "fp_layout", "fp_plan_create", "fp_plan_destroy", "fp_block_search",
-           "fp_threshold", "fp_sparse_prefill", "fp_dense_prefill")
+           "fp_threshold", "fp_search_select", "fp_sparse_prefill", "fp_dense_prefill")
 
 
 class fp_shape(ctypes.Structure):
@@ -56,6 +56,7 @@ def lib() -> ctypes.CDLL:
         L.fp_plan_destroy.restype = None
         L.fp_block_search.argtypes = [vp, vp, vp, f32, vp, vp]
         L.fp_threshold.argtypes = [vp, vp, ctypes.POINTER(fp_params), vp, vp, vp]
+        L.fp_search_select.argtypes = [vp, vp, vp, f32, ctypes.POINTER(fp_params), vp, vp, vp]
         L.fp_sparse_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.fp_dense_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp]
         _lib = L
@@ -134,7 +135,7 @@ class Plan:
         except Exception:
             pass
 
-    # --- the four compute calls --------------------------------------------------------------
+    # --- the compute calls --------------------------------------------------------------------
     def fp_block_search(self, Q, K, scores=None, eps: float = 1e-10, stream=None):
         import torch
         q = _dev_ptr(Q, torch.bfloat16, (self.T, self.hq, self.head_dim), "Q")
@@ -157,6 +158,22 @@ class Plan:
         c = _dev_ptr(cnt, torch.int32, (self.hq, self.m_total), "cnt")
         prm = fp_params(float(alpha), int(sink_tokens), int(window_tokens))
         _check(lib().fp_threshold(self._h, s, ctypes.byref(prm), i, c, _stream_ptr(stream)), "fp_threshold")
+        return idx, cnt
+
+    def fp_search_select(self, Q, K, alpha: float, sink_tokens: int = 256, window_tokens: int = 512, idx=None,
+                         cnt=None, eps: float = 1e-10, stream=None):
+        import torch
+        q = _dev_ptr(Q, torch.bfloat16, (self.T, self.hq, self.head_dim), "Q")
+        k = _dev_ptr(K, torch.bfloat16, (self.T, self.hkv, self.head_dim), "K")
+        if idx is None:
+            idx = torch.empty((self.hq, self.m_total, self.n_max), dtype=torch.int32, device=Q.device)
+        if cnt is None:
+            cnt = torch.empty((self.hq, self.m_total), dtype=torch.int32, device=Q.device)
+        i = _dev_ptr(idx, torch.int32, (self.hq, self.m_total, self.n_max), "idx")
+        c = _dev_ptr(cnt, torch.int32, (self.hq, self.m_total), "cnt")
+        prm = fp_params(float(alpha), int(sink_tokens), int(window_tokens))
+        _check(lib().fp_search_select(self._h, q, k, float(eps), ctypes.byref(prm), i, c, _stream_ptr(stream)),
+               "fp_search_select")
         return idx, cnt
 
     def _qkv(self, Q, K, V):

@@ -156,7 +156,9 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
     ok = ok && hipMemcpy(p->d_blk, blk.data(), blk.size() * sizeof(fp::BlockRec), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_order, order.data(), order.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_blk_ranked, blk_ranked.data(), blk.size() * sizeof(fp::BlockRec), hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel),
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel),
                                    hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -183,24 +185,52 @@ static bool on_plan_device(const fp_plan *p) {
     return hipGetDevice(&cur) == hipSuccess && cur == p->device;
 }
 
-fp_status fp_block_search(fp_plan *p, const void *Q, const void *K, float eps, float *scores, void *hip_stream) {
-    if (p == nullptr || Q == nullptr || K == nullptr || scores == nullptr || !(eps >= 0.f)) return FP_ERR_INVALID_ARG;
+// Alg. 1 stage 1 and stages 2-3; `sel` non-null selects the variant that applies Alg. 2 in place.
+static fp_status launch_search(fp_plan *p, const void *Q, const void *K, float eps, float *scores,
+                               const fp::SelectArgs *sel, void *hip_stream) {
     if (!on_plan_device(p)) return FP_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     fp::pool_k_kernel<<<dim3(p->m_total, p->hkv), 256, 0, st>>>(static_cast<const uint16_t *>(K), p->d_blk, p->hkv,
                                                                  p->d_kb_hi, p->d_kb_lo);
     const int nchunk = (p->g + fp::kSearchHeads - 1) / fp::kSearchHeads;
-    fp::search_kernel<<<dim3(p->m_total * p->hkv * nchunk), 256, p->search_lds, st>>>(
-        static_cast<const uint16_t *>(Q), p->d_kb_hi, p->d_kb_lo, p->d_blk_ranked, p->d_order, p->m_total, p->n_max, p->n_pad,
-        p->hq, p->hkv, p->g, nchunk, p->c, eps, scores);
+    const dim3 grid(p->m_total * p->hkv * nchunk);
+    const uint16_t *q = static_cast<const uint16_t *>(Q);
+    if (sel != nullptr)
+        fp::search_kernel<true><<<grid, 256, p->search_lds, st>>>(q, p->d_kb_hi, p->d_kb_lo, p->d_blk_ranked, p->d_order,
+                                                                  p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
+                                                                  p->c, eps, nullptr, *sel);
+    else
+        fp::search_kernel<false><<<grid, 256, p->search_lds, st>>>(q, p->d_kb_hi, p->d_kb_lo, p->d_blk_ranked, p->d_order,
+                                                                   p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
+                                                                   p->c, eps, scores, fp::SelectArgs{});
     return launch_status();
+}
+
+static bool params_ok(const fp_params *params) {
+    return params != nullptr && params->sink_tokens >= 0 && params->window_tokens >= 0 && params->alpha == params->alpha;
+}
+
+fp_status fp_block_search(fp_plan *p, const void *Q, const void *K, float eps, float *scores, void *hip_stream) {
+    if (p == nullptr || Q == nullptr || K == nullptr || scores == nullptr || !(eps >= 0.f)) return FP_ERR_INVALID_ARG;
+    return launch_search(p, Q, K, eps, scores, nullptr, hip_stream);
+}
+
+fp_status fp_search_select(fp_plan *p, const void *Q, const void *K, float eps, const fp_params *params, int32_t *idx,
+                           int32_t *cnt, void *hip_stream) {
+    if (p == nullptr || Q == nullptr || K == nullptr || idx == nullptr || cnt == nullptr || !(eps >= 0.f) || !params_ok(params))
+        return FP_ERR_INVALID_ARG;
+    fp::SelectArgs sel;
+    sel.alpha = params->alpha;
+    sel.sinkB = (params->sink_tokens + fp::kBlock - 1) / fp::kBlock;
+    sel.winB = (params->window_tokens + fp::kBlock - 1) / fp::kBlock;
+    sel.idx = idx;
+    sel.cnt = cnt;
+    return launch_search(p, Q, K, eps, nullptr, &sel, hip_stream);
 }
 
 fp_status fp_threshold(fp_plan *p, const float *scores, const fp_params *params, int32_t *idx, int32_t *cnt,
                        void *hip_stream) {
-    if (p == nullptr || scores == nullptr || params == nullptr || idx == nullptr || cnt == nullptr)
-        return FP_ERR_INVALID_ARG;
-    if (params->sink_tokens < 0 || params->window_tokens < 0 || !(params->alpha == params->alpha))
+    if (p == nullptr || scores == nullptr || idx == nullptr || cnt == nullptr || !params_ok(params))
         return FP_ERR_INVALID_ARG;
     if (!on_plan_device(p)) return FP_ERR_DEVICE;
     const int sinkB = (params->sink_tokens + fp::kBlock - 1) / fp::kBlock;

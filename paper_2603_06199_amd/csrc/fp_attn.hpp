@@ -101,11 +101,17 @@ __device__ __forceinline__ float attn_rowmax(const f32x16 &s0, const f32x16 &s1)
     return fmaxf(tm, __shfl_xor(tm, 32));
 }
 
-// Online-softmax bookkeeping for a new tile max: the accumulator and the row sum are rescaled
-// only when some row's max moved (wave-uniform test).
+// Online-softmax bookkeeping for a new tile max.  m_run is the reference point of the
+// exponentials, not necessarily the true running max: it is moved (and the accumulator and the
+// row sum rescaled) only when some row's max has outgrown it by more than kAttnLazy in the base-2
+// exponent (wave-uniform test).  Until then p = 2^(c*s - c*m_run) may reach 2^kAttnLazy, which
+// fp32 sums and bf16 operands hold without loss; O = acc / l and lse = c*m_run + log2 l do not
+// depend on the reference point.  With 32 rows per wave an exact-max rule would fire on most
+// tiles of a short row; this one fires a few times per row at most.
+constexpr float kAttnLazy = 8.0f;
 __device__ __forceinline__ void attn_new_max(float tm, float c, float &m_run, float &l_run, f32x16 (&acc)[4]) {
     const float m_new = fmaxf(m_run, tm);
-    if (__ballot(m_new > m_run)) {
+    if (__ballot((m_new - m_run) * c > kAttnLazy)) {
         const float a = fast_exp2((m_run - m_new) * c);
         l_run *= a;
 #pragma unroll
@@ -272,7 +278,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
-    float m_run = -INFINITY;   // running row max of the raw dot products (before scaling by c)
+    float m_run = -INFINITY;   // reference point of the exponentials (raw dot-product units), see attn_new_max
     float l_run = 0.f;         // this lane's share of the running row sum
 
     // Fragment addresses inside a buffer.  K: rows l%32 and 32 + l%32, chunk (2ks + half) ^ (row & 15).

@@ -129,10 +129,19 @@ __device__ __forceinline__ float2 search_merge(float2 a, float2 b) {
     return make_float2(m, sa + sb);
 }
 
+// Selection parameters of the fused variant (Alg. 2 applied to the row while it is still in LDS).
+struct SelectArgs {
+    float alpha;
+    int sinkB, winB;
+    int32_t *idx, *cnt;
+};
+
+template <bool SELECT>
 __global__ __launch_bounds__(256, 4) void search_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ kb_hi, const uint16_t *__restrict__ kb_lo,
     const BlockRec *__restrict__ blk_ranked, const int32_t *__restrict__ order, int m_total, int n_max, int n_pad,
-    int hq, int hkv, int g, int nchunk, float c /* tau*log2(e) */, float eps, float *__restrict__ scores) {
+    int hq, int hkv, int g, int nchunk, float c /* tau*log2(e) */, float eps, float *__restrict__ scores,
+    SelectArgs sel) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     float2 *mbox = reinterpret_cast<float2 *>(smem + kSearchBufs * kSearchTile);
     float2 *ms_all = reinterpret_cast<float2 *>(smem + kSearchStageBytes);
@@ -246,6 +255,7 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     }
     __syncthreads();
     if (!active) return;
+    if (SELECT && qh) return;   // the list is compacted by one wave per head
     // Eq. 3-4: row max of the pair maxima, rescale, normalise; each wave writes half of the columns.
     float M = -INFINITY;
     for (int J = l; J <= I; J += 64) M = fmaxf(M, ms[J].x);
@@ -257,15 +267,41 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     }
     tot = wave_sum(tot);
     const float denom = tot + eps;
-    float *out = scores + ((size_t)h * m_total + r) * n_max;
-    for (int J = l + 64 * qh; J < n_max; J += 128) {
-        float p = 0.f;
-        if (J <= I) {
-            const float2 v = ms[J];
-            p = (v.y * fast_exp2(v.x - M)) / denom;
+    if (!SELECT) {
+        float *out = scores + ((size_t)h * m_total + r) * n_max;
+        for (int J = l + 64 * qh; J < n_max; J += 128) {
+            float p = 0.f;
+            if (J <= I) {
+                const float2 v = ms[J];
+                p = (v.y * fast_exp2(v.x - M)) / denom;
+            }
+            out[J] = p;
         }
-        out[J] = p;
+        return;
     }
+    // Fused Alg. 2: the normalised scores (the same fp32 expression as above, so the decisions are
+    // those of the two-kernel path) replace the row's maxima in LDS; threshold from their max;
+    // ballot compaction as in threshold_kernel below.  Each lane re-reads only what it wrote.
+    float mx = -INFINITY;
+    for (int J = l; J <= I; J += 64) {
+        const float2 v = ms[J];
+        const float p = (v.y * fast_exp2(v.x - M)) / denom;
+        ms[J].x = p;
+        mx = fmaxf(mx, p);
+    }
+    mx = wave_max(mx);
+    const float thr = __fmul_rn(sel.alpha, mx);
+    int32_t *lst = sel.idx + ((size_t)h * m_total + r) * n_max;
+    int count = 0;
+    for (int base = 0; base <= I; base += 64) {
+        const int J = base + l;
+        bool keep = false;
+        if (J <= I) keep = (ms[J].x >= thr) || (J < sel.sinkB) || (I - J < sel.winB);
+        const unsigned long long bal = __ballot(keep);
+        if (keep) lst[count + __builtin_popcountll(bal & ((1ull << l) - 1ull))] = J;
+        count += __builtin_popcountll(bal);
+    }
+    if (l == 0) sel.cnt[(size_t)h * m_total + r] = count;
 }
 
 // ---------------------------------------------------------------------------------------------

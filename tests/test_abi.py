@@ -66,9 +66,10 @@ def test_null_arguments(lib):
     assert lib.fp_layout(None, None, None, None) == B.FP_ERR_INVALID_ARG
     s, keep = B.make_shape([0, 128], 4, 1)
     assert lib.fp_plan_create(ctypes.byref(s), 0, None) == B.FP_ERR_INVALID_ARG
-    for call, nargs in ((lib.fp_block_search, 6), (lib.fp_threshold, 6), (lib.fp_sparse_prefill, 9), (lib.fp_dense_prefill, 7)):
+    for call, nargs in ((lib.fp_block_search, 6), (lib.fp_threshold, 6), (lib.fp_search_select, 8),
+                        (lib.fp_sparse_prefill, 9), (lib.fp_dense_prefill, 7)):
         args = [None] * nargs
-        if call is lib.fp_block_search:
+        if call in (lib.fp_block_search, lib.fp_search_select):
             args[3] = 0.0
         assert call(*args) == B.FP_ERR_INVALID_ARG
     lib.fp_plan_destroy(None)   # documented no-op

@@ -53,6 +53,15 @@ def _sampled_checks(r, rows_scores, rows_attn, rows_dense):
     compare_scores(P_gpu, P_ref, cu, rows=rows_scores)
     nd, nb = compare_lists_banded(r["idx"].cpu().numpy(), r["cnt"].cpu().numpy(), P_ref, cu, w.alpha, rows=rows_scores)
     print(f"{w.name}: {len(rows_scores)} sampled rows: list mismatches {nd}, pairs in the near-threshold band {nb}")
+    # the one-pass entry point: same band rule against the oracle on the sampled rows, and on every
+    # row the same lists as the two calls above
+    idx_f, cnt_f = r["plan"].fp_search_select(r["dQ"], r["dK"], w.alpha)
+    torch.cuda.synchronize()
+    compare_lists_banded(idx_f.cpu().numpy(), cnt_f.cpu().numpy(), P_ref, cu, w.alpha, rows=rows_scores)
+    assert torch.equal(cnt_f, r["cnt"])
+    valid = torch.arange(idx_f.shape[2], device="cuda")[None, None, :] < cnt_f[:, :, None]
+    assert bool((idx_f == r["idx"])[valid].all())
+    del idx_f, cnt_f, valid
     # sparse attention on the GPU's own lists vs the oracle given the same lists
     idx_h, cnt_h = r["idx"].cpu().numpy(), r["cnt"].cpu().numpy()
     O_ref, lse_ref = oracle.sparse_prefill(r["Q"], r["K"], r["V"], cu, idx_h, cnt_h, rows=rows_attn)

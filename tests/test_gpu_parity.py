@@ -73,6 +73,22 @@ def test_search_plus_threshold_lists(case):
     print(f"list mismatches {nd} (all inside the near-threshold band of {nb} pairs)")
 
 
+def test_fused_search_select_lists(case):
+    """The one-pass entry point against the oracle's Alg. 1 + Alg. 2 (same band rule as above), for the
+    default and a second sink/window setting; it must also agree entry by entry with the library's
+    own two-call path, whose decisions it is documented to reproduce."""
+    plan, w = case["plan"], case["w"]
+    for alpha, sink, win in ((w.alpha, 256, 512), (0.3, 100, 200), (0.0, 0, 0)):
+        idx, cnt = plan.fp_search_select(case["dQ"], case["dK"], alpha, sink_tokens=sink, window_tokens=win)
+        torch.cuda.synchronize()
+        nd, nb = compare_lists_banded(idx.cpu().numpy(), cnt.cpu().numpy(), case["P_ref"], case["cu"], alpha,
+                                      sink_tokens=sink, window_tokens=win)
+        idx2, cnt2 = plan.fp_threshold(plan.fp_block_search(case["dQ"], case["dK"]), alpha, sink_tokens=sink,
+                                       window_tokens=win)
+        torch.cuda.synchronize()
+        compare_lists_exact(idx.cpu().numpy(), cnt.cpu().numpy(), idx2.cpu().numpy(), cnt2.cpu().numpy())
+
+
 def test_sparse_prefill_matches_oracle_on_oracle_lists(case):
     cu = case["cu"]
     idx_r, cnt_r = oracle.threshold(case["P_ref"], cu, case["w"].alpha)
