@@ -98,7 +98,7 @@ __device__ __forceinline__ float attn_rowmax(const f32x16 &s0, const f32x16 &s1)
         tb = max3(tb, s1[i], s1[i + 1]);
     }
     const float tm = max3(ta, s0[15], fmaxf(tb, s1[15]));
-    return fmaxf(tm, __shfl_xor(tm, 32));
+    return halves_max(tm);
 }
 
 // Online-softmax bookkeeping for a new tile max.  m_run is the reference point of the
@@ -380,7 +380,7 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     // through LDS (its own 8 KB of the K buffers: their last reader and their last incoming load
     // finished before the barrier of the last-but-one step) into 16-byte pieces, 16 lanes per row.
     // Chunk c of row q is kept at chunk c ^ (q & 15) so that neither side meets a bank conflict.
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float l_tot = halves_sum(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     {
         char *ob = smem + w * (32 * kAttnRowBytes);

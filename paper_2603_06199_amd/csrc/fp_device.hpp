@@ -34,6 +34,30 @@ __device__ __forceinline__ f32x16 mfma32(bf16x8 a, bf16x8 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
 }
 
+// Combine each lane's value with that of lane l ^ 32 through the register swap between the two
+// halves of the wave (v_permlane32_swap exchanges the upper half of its first operand with the
+// lower half of its second): applied to two copies of x, one register ends up with x[l % 32] and
+// the other with x[32 + l % 32] in every lane.  Unlike a shuffle through the LDS crossbar this
+// leaves the LDS queue alone, so no wait on outstanding fragment reads is needed around it.
+// Written as inline assembly because the compiler's builtin folds the two results into one when
+// both inputs are the same value; the s_nop covers the wait states the instruction needs after
+// a VALU write of its operands.
+__device__ __forceinline__ void halves_swap(float x, float &lo, float &hi) {
+    lo = x;
+    hi = x;
+    asm("s_nop 1\n\tv_permlane32_swap_b32 %0, %1" : "+v"(lo), "+v"(hi));
+}
+__device__ __forceinline__ float halves_max(float x) {
+    float a, b;
+    halves_swap(x, a, b);
+    return fmaxf(a, b);
+}
+__device__ __forceinline__ float halves_sum(float x) {
+    float a, b;
+    halves_swap(x, a, b);
+    return a + b;
+}
+
 __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));

@@ -107,7 +107,7 @@ __device__ __forceinline__ float2 search_reduce(f32x16 (&acc)[2], float c, int n
         mx = max3(mx, acc[0][i], acc[1][i]);
         mx = max3(mx, acc[0][i + 1], acc[1][i + 1]);
     }
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    mx = halves_max(mx);
     const float mc = mx * c;
     const float mcs = RAGGED ? (mx == -INFINITY ? 0.f : mc) : mc;   // all queries missing: every term is 2^-inf = 0
     float s0 = 0.f, s1 = 0.f;
@@ -117,7 +117,7 @@ __device__ __forceinline__ float2 search_reduce(f32x16 (&acc)[2], float c, int n
         s1 += fast_exp2(__builtin_fmaf(acc[1][i], c, -mcs));
     }
     float sum = s0 + s1;
-    sum += __shfl_xor(sum, 32);
+    sum = halves_sum(sum);
     return make_float2(mc, sum);
 }
 
