@@ -50,8 +50,10 @@ def causal_pairs(row_offset, hq):
     return int((n * (n + 1) // 2).sum()) * hq
 
 
-def run_workload(w, steps, warmup, dense_runs, torch, B):
-    """Times the path on one workload; returns a dict of measurements (times in ms)."""
+def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0):
+    """Times the path on one workload; returns a dict of measurements (times in ms).  With
+    min_timed_ms > 0 (the length sweep) short workloads take more warm-up and timed steps, so that
+    the timed region lasts at least that long and the clocks have settled."""
     from paper_2603_06199_amd import synth
     t0 = time.time()
     Q, K, V = synth.make_qkv(w, threads=min(16, os.cpu_count() or 8))
@@ -78,6 +80,15 @@ def run_workload(w, steps, warmup, dense_runs, torch, B):
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    if min_timed_ms > 0:
+        t_probe = time.perf_counter()
+        step()
+        torch.cuda.synchronize()
+        one_ms = max((time.perf_counter() - t_probe) * 1e3, 1e-3)
+        steps = max(steps, min(500, int(np.ceil(min_timed_ms / one_ms))))
+        for _ in range(min(steps, 100)):
+            step()
+        torch.cuda.synchronize()
     evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(steps)]
     t_start = time.perf_counter()
     for i in range(steps):
@@ -94,6 +105,12 @@ def run_workload(w, steps, warmup, dense_runs, torch, B):
         Od = torch.empty_like(dQ)
         plan.fp_dense_prefill(dQ, dK, dV, Od, lse)
         torch.cuda.synchronize()
+        if min_timed_ms > 0:
+            t_probe = time.perf_counter()
+            plan.fp_dense_prefill(dQ, dK, dV, Od, lse)
+            torch.cuda.synchronize()
+            one_ms = max((time.perf_counter() - t_probe) * 1e3, 1e-3)
+            dense_runs = max(dense_runs, min(500, int(np.ceil(min_timed_ms / one_ms))))
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(dense_runs):
@@ -119,7 +136,7 @@ def run_workload(w, steps, warmup, dense_runs, torch, B):
     search_bytes = 2 * T * 128 * (w.hq + w.hkv) + 4 * pairs          # Q once + K once + one fp32 per causal pair
     thr_bytes = 4 * pairs + 4 * kept + 4 * hq * m
     res = dict(
-        workload=w.name, tokens=T, hq=w.hq, hkv=w.hkv, alpha=w.alpha, planting=w.mode,
+        workload=w.name, tokens=T, hq=w.hq, hkv=w.hkv, alpha=w.alpha, planting=w.mode, timed_steps=steps,
         ms=dict(search=float(search_ms), threshold=float(thr_ms), sparse_attention=float(sparse_ms),
                 end_to_end=float(search_ms + thr_ms + sparse_ms), end_to_end_wall=float(wall_ms),
                 search_select_fused=float(fused_ms), end_to_end_fused=float(fused_ms + sparse_ms), dense=dense_ms),
@@ -258,8 +275,8 @@ def main():
         rows = []
         for L in (4096, 8192, 16384, 32768, 65536, 131072, 262144, 524288):
             wl = dataclasses.replace(synth.config(1, "coherent"), seqlens=(L,), name=f"qwen3_shape_{L // 1024}k_coherent")
-            r, h = run_workload(wl, a.steps, a.warmup, dense_runs=2, torch=torch, B=B)
-            r["forced_density"] = [forced_density_run(wl, h, d, a.steps, torch) for d in (0.6, 0.06)]
+            r, h = run_workload(wl, a.steps, a.warmup, dense_runs=2, torch=torch, B=B, min_timed_ms=100.0)
+            r["forced_density"] = [forced_density_run(wl, h, d, r["timed_steps"], torch) for d in (0.6, 0.06)]
             log(f"[bench] sweep {json.dumps(r)}")
             rows.append(r)
             del h
@@ -297,6 +314,7 @@ def main():
         sup, host2 = run_workload(ws, a.steps, a.warmup, dense_runs=0, torch=torch, B=B)
         sup["ms"]["dense"] = dense_ms            # same shape: the dense kernel's time does not depend on values
         sup["speedup_vs_own_dense"] = dense_ms / sup["ms"]["end_to_end"]
+        sup["speedup_vs_own_dense_fused"] = dense_ms / sup["ms"]["end_to_end_fused"]
         if not a.no_cpu_baseline:
             sup["cpu_baseline"] = cpu_baseline(ws, host2, sup, torch)
         log(f"[bench] supplementary {json.dumps(sup)}")

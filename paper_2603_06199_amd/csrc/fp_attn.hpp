@@ -211,13 +211,17 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
 
 #define FP_TILE_BLOCK(t) attn_tile_block<SPARSE>(list, (t), I)
 
-    // Q^T B-fragments: query 32w + l%32, dims 16ks + 8*half..+7.
+    // Q^T B-fragments: query 32w + l%32, dims 16ks + 8*half..+7.  The loads are written as
+    // assembly so that their completion is counted here and not by the compiler, which cannot see
+    // the tile loads queued behind them and would wait for those too: the prologue waits once,
+    // with the exact count, for the fragments and the first K tile together.
     bf16x8 qb[8];
     {
         int row = q_local < bi.y ? q_local : bi.y - 1;
         const uint16_t *qp = Q + ((size_t)(bi.x + row) * hq + h) * kHeadDim + 8 * half;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qb[ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
+        for (int ks = 0; ks < 8; ++ks)
+            asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=&v"(qb[ks]) : "v"(qp), "n"(32 * ks) : "memory");
     }
 
     // Tile loads.  One wave-wide instruction moves 4 rows (1 KB); wave w loads rows 16w + 4i + l/16
@@ -299,21 +303,21 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     // query); elsewhere nothing is masked.
 #define FP_LIM(t) (FP_TILE_BLOCK(t) == I ? q_local - ((t) & 1) * kAttnTileKeys - 4 * half : 2 * kAttnTileKeys)
 
-    // Prologue: K[0], V[0], K[1] landed, K[2] on its way; S^T of tile 0 with its row max.
+    // Prologue: S^T of tile 0 with its row max; on leaving it K[1] and V[0] are in, K[2] on its way.
     FP_LOAD(false, Kb, ld_kcol, b0, 0, FP_KBUF(0));
     FP_LOAD(false, Vb, ld_vcol, b0, 0, FP_VBUF(0));
-    // Pin the Q fragments: their loads are issued by now and are older than everything the loop
-    // waits for, so no wait on them can end up between the loop's MFMAs.
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[ks]));
     FP_LOAD(false, Kb, ld_kcol, b0, 1, FP_KBUF(1));   // ntiles >= 2
     FP_LOAD(false, Kb, ld_kcol, (nb > 1 ? b1 : b0), (nb > 1 ? 0 : 1), FP_KBUF(2));
-    FP_WAIT_VMCNT(4);
+    FP_WAIT_VMCNT(12);   // Q and K[0] are in; V[0] and K[1] keep landing under the first QK^T
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[ks]));   // uses of Q stay behind the wait
     __syncthreads();
     f32x16 sA0, sA1, sB0, sB1;
     attn_qk(smem, FP_KBUF(0) + k_frag, qb, sA0, sA1);
     attn_mask(sA0, sA1, b0 == I ? q_local - 4 * half : 2 * kAttnTileKeys);
     m_run = attn_rowmax(sA0, sA1);   // finite: key 0 of tile 0 is visible to every query
+    FP_WAIT_VMCNT(4);
+    __syncthreads();
 
     // Step t.  On entry K[t+1] and V[t] are complete in LDS, K[t+2] may still be landing, S^T(t) is
     // in (c0, c1) and its row max is already folded into m_run (accumulator rescaled).  The step
