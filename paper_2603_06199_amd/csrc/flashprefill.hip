@@ -124,7 +124,7 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
     const float tau = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
     p->c = tau * fp::kLog2e;
     p->n_pad = (L.n_max + 31) / 32 * 32;
-    p->search_lds = (size_t)fp::kSearchStageBytes + (size_t)fp::kSearchHeads * p->n_pad * sizeof(float2);
+    p->search_lds = (size_t)fp::kSearchStageBytes + fp::kSearchRowHeader + (size_t)fp::kSearchHeads * p->n_pad * sizeof(float);
 
     std::vector<fp::BlockRec> blk((size_t)L.m_total);
     for (int s = 0; s < shape->nseq; ++s) {

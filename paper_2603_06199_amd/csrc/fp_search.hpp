@@ -55,10 +55,10 @@ __global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict_
 // pooled key per lane column, so the reduction over the query axis (Eq. 1-2: max, then sum of
 // 2^(x - max)) is in-register plus one lane exchange.  The two waves of a head then merge their
 // (max, sum) pairs through a small LDS mailbox, one step later.  Registers and LDS leave room
-// for two to four workgroups per CU (up to about 2900 blocks per sequence for two): waves of
+// for two to four workgroups per CU (two at 4096 blocks per sequence, four up to 1000): waves of
 // different workgroups share a SIMD without sharing a barrier, so one's MFMAs overlap the
-// other's reduction.  (m, S) per block pair stay in LDS; after the last
-// tile the row max is taken, the row rescaled (Eq. 3), normalised (Eq. 4) and written once.
+// other's reduction.  Each block pair's (m, S) is kept in LDS as one float, m + log2 S; after the
+// last tile the row is brought to a common reference (Eq. 3), normalised (Eq. 4) and written once.
 // Nothing of size L x L/B ever exists.
 // ---------------------------------------------------------------------------------------------
 constexpr int kSearchPlane = 32 * 256;                 // one plane (hi or lo) of a 32-row tile, unpadded
@@ -67,6 +67,7 @@ constexpr int kSearchBufs = 2;
 constexpr int kSearchHeads = 2;                        // query heads per workgroup
 constexpr int kSearchMailbox = 2 * kSearchHeads * 32 * 8;   // [step parity][head][pooled key] (max, sum)
 constexpr int kSearchStageBytes = kSearchBufs * kSearchTile + kSearchMailbox;
+constexpr int kSearchRowHeader = 16;                   // per-head row maxima, ahead of the rows
 
 // 64 x 32 logits of one pooled-key tile: acc[qt] = Q[qt] (hi + lo)^T.  baddr = buffer base + the
 // lane's row and swizzled chunk for k-slice 0 (slice ks sits at baddr ^ (ks << 5)).
@@ -144,7 +145,8 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     SelectArgs sel) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     float2 *mbox = reinterpret_cast<float2 *>(smem + kSearchBufs * kSearchTile);
-    float2 *ms_all = reinterpret_cast<float2 *>(smem + kSearchStageBytes);
+    float *mtop = reinterpret_cast<float *>(smem + kSearchStageBytes);   // [head] max of the row's pair maxima
+    float *ms_all = mtop + kSearchRowHeader / sizeof(float);
 
     const int per_row = hkv * nchunk;
     const int rank = blockIdx.x / per_row;
@@ -159,7 +161,7 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     const int hg = ch * kSearchHeads + hd;
     const bool active = hg < g;
     const int h = hk * g + (active ? hg : g - 1);
-    float2 *ms = ms_all + (size_t)hd * n_pad;
+    float *ms = ms_all + (size_t)hd * n_pad;   // the row: t_J = m_J + log2 S_J per block pair
 
     // Query fragments: qa[qt][ks] covers queries 64qh + 32qt + l%32, dims 16ks + 8(l/32)..+7.
     bf16x8 qa[2][8];
@@ -217,6 +219,7 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     // posts its (max, sum) in the mailbox, the lower half merges the previous tile's post with
     // its own pair from the previous step and files the result; wait for tile jt+1.
     float2 prev = make_float2(-INFINITY, 0.f);
+    float m_top = -INFINITY;
 #define FP_STEP(RAGGED, jt)                                                                               \
     do {                                                                                                  \
         const int jt_ = (jt);                                                                             \
@@ -230,7 +233,11 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
                     mbox[((jt_ & 1) * kSearchHeads + hd) * 32 + l] = v_;                                             \
                 } else {                                                                                  \
                     const int Jp_ = 32 * (jt_ - 1) + l;                                                   \
-                    if (jt_ > 0 && Jp_ <= I) ms[Jp_] = search_merge(prev, mbox[(((jt_ - 1) & 1) * kSearchHeads + hd) * 32 + l]); \
+                    if (jt_ > 0 && Jp_ <= I) {                                                            \
+                        const float2 mg_ = search_merge(prev, mbox[(((jt_ - 1) & 1) * kSearchHeads + hd) * 32 + l]); \
+                        ms[Jp_] = mg_.x + __log2f(mg_.y);                                                 \
+                        m_top = fmaxf(m_top, mg_.x);                                                      \
+                    }                                                                                     \
                     prev = v_;                                                                            \
                 }                                                                                         \
             }                                                                                             \
@@ -249,44 +256,42 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
 #undef FP_STEP
     // the last tile's merge (its post is behind the loop's final barrier), then everyone meets once
     // more so that both waves of a head see the complete (m, S) row
-    if (active && qh == 0 && l < 32) {
+    if (active && qh == 0) {
         const int Jp = 32 * (ntile - 1) + l;
-        if (Jp <= I) ms[Jp] = search_merge(prev, mbox[(((ntile - 1) & 1) * kSearchHeads + hd) * 32 + l]);
+        if (l < 32 && Jp <= I) {
+            const float2 mg = search_merge(prev, mbox[(((ntile - 1) & 1) * kSearchHeads + hd) * 32 + l]);
+            ms[Jp] = mg.x + __log2f(mg.y);
+            m_top = fmaxf(m_top, mg.x);
+        }
+        m_top = wave_max(m_top);
+        if (l == 0) mtop[hd] = m_top;
     }
     __syncthreads();
     if (!active) return;
     if (SELECT && qh) return;   // the list is compacted by one wave per head
-    // Eq. 3-4: row max of the pair maxima, rescale, normalise; each wave writes half of the columns.
-    float M = -INFINITY;
-    for (int J = l; J <= I; J += 64) M = fmaxf(M, ms[J].x);
-    M = wave_max(M);
+    // Eq. 3-4.  With M the max of the row's pair maxima, S'_J = S_J 2^(m_J - M) and the score is
+    // S'_J / (sum_K S'_K + eps).  The row holds t_J = m_J + log2 S_J (half the LDS of the pair), so
+    // the same ratio is formed relative to T = max_J t_J: S'_J = 2^(t_J - T) * 2^(T - M), i.e.
+    // score_J = 2^(t_J - T) / (sum_K 2^(t_K - T) + eps * 2^(M - T)), where M <= T because S_J >= 1.
+    float Tm = -INFINITY;
+    for (int J = l; J <= I; J += 64) Tm = fmaxf(Tm, ms[J]);
+    Tm = wave_max(Tm);
     float tot = 0.f;
-    for (int J = l; J <= I; J += 64) {
-        const float2 v = ms[J];
-        tot += v.y * fast_exp2(v.x - M);
-    }
+    for (int J = l; J <= I; J += 64) tot += fast_exp2(ms[J] - Tm);
     tot = wave_sum(tot);
-    const float denom = tot + eps;
-    if (!SELECT) {
+    const float denom = tot + eps * fast_exp2(mtop[hd] - Tm);
+    if (!SELECT) {   // each wave writes half of the columns
         float *out = scores + ((size_t)h * m_total + r) * n_max;
-        for (int J = l + 64 * qh; J < n_max; J += 128) {
-            float p = 0.f;
-            if (J <= I) {
-                const float2 v = ms[J];
-                p = (v.y * fast_exp2(v.x - M)) / denom;
-            }
-            out[J] = p;
-        }
+        for (int J = l + 64 * qh; J < n_max; J += 128) out[J] = J <= I ? fast_exp2(ms[J] - Tm) / denom : 0.f;
         return;
     }
     // Fused Alg. 2: the normalised scores (the same fp32 expression as above, so the decisions are
-    // those of the two-kernel path) replace the row's maxima in LDS; threshold from their max;
-    // ballot compaction as in threshold_kernel below.  Each lane re-reads only what it wrote.
+    // those of the two-kernel path) replace the row in LDS; threshold from their max; ballot
+    // compaction as in threshold_kernel below.  Each lane re-reads only what it wrote.
     float mx = -INFINITY;
     for (int J = l; J <= I; J += 64) {
-        const float2 v = ms[J];
-        const float p = (v.y * fast_exp2(v.x - M)) / denom;
-        ms[J].x = p;
+        const float p = fast_exp2(ms[J] - Tm) / denom;
+        ms[J] = p;
         mx = fmaxf(mx, p);
     }
     mx = wave_max(mx);
@@ -296,7 +301,7 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     for (int base = 0; base <= I; base += 64) {
         const int J = base + l;
         bool keep = false;
-        if (J <= I) keep = (ms[J].x >= thr) || (J < sel.sinkB) || (I - J < sel.winB);
+        if (J <= I) keep = (ms[J] >= thr) || (J < sel.sinkB) || (I - J < sel.winB);
         const unsigned long long bal = __ballot(keep);
         if (keep) lst[count + __builtin_popcountll(bal & ((1ull << l) - 1ull))] = J;
         count += __builtin_popcountll(bal);
