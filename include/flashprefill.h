@@ -94,7 +94,7 @@ fp_status fp_block_search(fp_plan *plan, const void *Q, const void *K, float eps
  * keep J iff (scores >= thresh or J < sink blocks or 0 <= I-J < window blocks) and J <= I;
  * idx[h, r, 0..cnt[h, r]) holds the kept J in ascending order.  Entries of idx past cnt are
  * not written (the paper pads them with the block count and sorts; the compaction here yields
- * the same prefix without a sort).  `scores` entries with J > I are never read.
+ * the same prefix without a sort).  `scores` entries with J > I do not affect the result.
  */
 fp_status fp_threshold(fp_plan *plan, const float *scores, const fp_params *params, int32_t *idx, int32_t *cnt,
                        void *hip_stream);

@@ -160,9 +160,11 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize,
-                                   (int)(fp::kThresholdWaves * ((L.n_max + 63) / 64 * 64) * sizeof(float))) == hipSuccess;
+    const int thr_lds = (int)(fp::kThresholdWaves * ((L.n_max + 63) / 64 * 64) * sizeof(float));
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel<true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, thr_lds) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel<false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, thr_lds) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<false>),
@@ -237,9 +239,15 @@ fp_status fp_threshold(fp_plan *p, const float *scores, const fp_params *params,
     const int winB = (params->window_tokens + fp::kBlock - 1) / fp::kBlock;
     const int rows = p->hq * p->m_total;
     const int n_pad = (p->n_max + 63) / 64 * 64;
-    fp::threshold_kernel<<<dim3((rows + fp::kThresholdWaves - 1) / fp::kThresholdWaves), 64 * fp::kThresholdWaves,
-                           (size_t)fp::kThresholdWaves * n_pad * sizeof(float), static_cast<hipStream_t>(hip_stream)>>>(
-        scores, p->d_blk, p->m_total, p->n_max, n_pad, p->hq, params->alpha, sinkB, winB, idx, cnt);
+    const dim3 grid((rows + fp::kThresholdWaves - 1) / fp::kThresholdWaves);
+    const size_t lds = (size_t)fp::kThresholdWaves * n_pad * sizeof(float);
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    if (p->n_max % 4 == 0 && reinterpret_cast<uintptr_t>(scores) % 16 == 0)
+        fp::threshold_kernel<true><<<grid, 64 * fp::kThresholdWaves, lds, st>>>(scores, p->d_blk, p->m_total, p->n_max, n_pad, p->hq,
+                                                                               params->alpha, sinkB, winB, idx, cnt);
+    else
+        fp::threshold_kernel<false><<<grid, 64 * fp::kThresholdWaves, lds, st>>>(scores, p->d_blk, p->m_total, p->n_max, n_pad, p->hq,
+                                                                                params->alpha, sinkB, winB, idx, cnt);
     return launch_status();
 }
 

@@ -318,6 +318,7 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
 // ---------------------------------------------------------------------------------------------
 constexpr int kThresholdWaves = 4;   // rows per workgroup
 
+template <bool VEC>   // VEC: rows start on 16-byte boundaries (n_max % 4 == 0, aligned base)
 __global__ __launch_bounds__(256) void threshold_kernel(const float *__restrict__ scores,
                                                         const BlockRec *__restrict__ blk, int m_total, int n_max,
                                                         int n_pad, int hq, float alpha, int sinkB, int winB,
@@ -334,10 +335,27 @@ __global__ __launch_bounds__(256) void threshold_kernel(const float *__restrict_
     int32_t *out = idx + (size_t)wave * n_max;
 
     float mx = -INFINITY;
-    for (int J = l; J <= I; J += 64) {
-        const float v = row[J];
-        buf[J] = v;
-        mx = fmaxf(mx, v);
+    if (VEC) {
+        // 16 bytes per lane and four loads in flight per wave; the last vector may reach up to three
+        // entries past the diagonal (still inside the row), which are left out of the max.
+        const float4 *row4 = reinterpret_cast<const float4 *>(row);
+        float4 *buf4 = reinterpret_cast<float4 *>(buf);
+#pragma unroll 4
+        for (int j4 = l; 4 * j4 <= I; j4 += 64) {
+            const float4 v = row4[j4];
+            buf4[j4] = v;
+            const int J = 4 * j4;
+            mx = fmaxf(mx, v.x);
+            if (J + 1 <= I) mx = fmaxf(mx, v.y);
+            if (J + 2 <= I) mx = fmaxf(mx, v.z);
+            if (J + 3 <= I) mx = fmaxf(mx, v.w);
+        }
+    } else {
+        for (int J = l; J <= I; J += 64) {
+            const float v = row[J];
+            buf[J] = v;
+            mx = fmaxf(mx, v);
+        }
     }
     mx = wave_max(mx);
     const float thr = __fmul_rn(alpha, mx);   // one fp32 rounding, as the reference decision
@@ -346,7 +364,7 @@ __global__ __launch_bounds__(256) void threshold_kernel(const float *__restrict_
     for (int base = 0; base <= I; base += 64) {
         const int J = base + l;
         bool keep = false;
-        if (J <= I) keep = (buf[J] >= thr) || (J < sinkB) || (I - J < winB);   // each lane re-reads what it wrote
+        if (J <= I) keep = (buf[J] >= thr) || (J < sinkB) || (I - J < winB);
         const unsigned long long bal = __ballot(keep);
         if (keep) out[count + __builtin_popcountll(bal & ((1ull << l) - 1ull))] = J;
         count += __builtin_popcountll(bal);

@@ -64,6 +64,18 @@ def test_threshold_other_sink_and_window(case):
         compare_lists_exact(idx.cpu().numpy(), cnt.cpu().numpy(), idx_r, cnt_r)
 
 
+def test_threshold_ignores_entries_past_the_diagonal(case):
+    """Scores with J > I are documented not to matter: poison them and expect the oracle's lists."""
+    from gpu_util import causal_mask
+    P_ref = case["P_ref"]
+    idx_r, cnt_r = oracle.threshold(P_ref, case["cu"], 0.25)
+    poisoned = np.where(causal_mask(case["cu"])[None], P_ref, np.float32(np.nan)).astype(np.float32)
+    poisoned[:, :, 1::2] = np.where(causal_mask(case["cu"])[None, :, 1::2], P_ref[:, :, 1::2], np.float32(3e38))
+    idx, cnt = case["plan"].fp_threshold(torch.from_numpy(poisoned).cuda(), 0.25)
+    torch.cuda.synchronize()
+    compare_lists_exact(idx.cpu().numpy(), cnt.cpu().numpy(), idx_r, cnt_r)
+
+
 def test_search_plus_threshold_lists(case):
     plan = case["plan"]
     P = plan.fp_block_search(case["dQ"], case["dK"])
