@@ -12,10 +12,16 @@
  * decided by floating point, so it is taken in fp32 on those fp32 scores, the
  * precision the GPU kernel decides in.
  *
- * Layout: Q [T, Hq, d], K and V [T, Hkv, d], token-major packed; sequence s owns
- * tokens cu[s]..cu[s+1]; blocks of `block` tokens are aligned to each sequence's
- * start; q-block row r = row_offset[s] + I.  scores/idx are [Hq, m_total, n_max],
- * cnt is [Hq, m_total], O is [T, Hq, d] (fp32 here), lse is [Hq, T].
+ * Layout: Q [T, Hq, d], K and V [Tk, Hkv, d], token-major packed; sequence s owns
+ * query tokens cu[s]..cu[s+1] and key tokens cuk[s]..cuk[s+1] (cuk == NULL: the
+ * same tokens, plain prefill).  With a KV prefix (chunked prefill) the queries are the
+ * last tokens of the sequence: query i of the chunk sits at position P + i, where
+ * P = kv_len - q_len >= 0 must be a multiple of `block`, and sees keys 0..P+i.
+ * Blocks of `block` tokens are aligned to each sequence's start, so q-block I of the
+ * chunk is the sequence's block I + P/block, and its causal key blocks are
+ * J <= I + P/block.  q-block row r = row_offset[s] + I.  scores/idx are
+ * [Hq, m_total, n_max] with n_max the most key blocks of any sequence, cnt is
+ * [Hq, m_total], O is [T, Hq, d] (fp32 here), lse is [Hq, T].
  *
  * Readings of points the paper leaves open are listed where they apply.
  * Pins: tests/test_oracle_*.py (closed forms, library softmax, brute force, invariants).
@@ -36,34 +42,56 @@ static inline double bf16_val(uint16_t b) {
 }
 
 typedef struct {
-    int nseq, m_total, n_max;
-    int *row_offset; /* nseq+1 */
+    int nseq, m_total, n_max, kb_total;
+    int *row_offset; /* nseq+1: first q-block row of each sequence */
+    int *kb_offset;  /* nseq+1: first key block of each sequence (in the list of all key blocks) */
+    int *pb;         /* nseq: prefix length in blocks */
     int *row_seq;    /* m_total: sequence of each q-block row */
+    const int32_t *cuq, *cuk;
 } rows_t;
-
-static int rows_init(rows_t *R, int nseq, const int32_t *cu, int block) {
-    R->nseq = nseq;
-    R->row_offset = (int *)malloc(sizeof(int) * (size_t)(nseq + 1));
-    if (!R->row_offset) return -1;
-    R->row_offset[0] = 0;
-    R->n_max = 0;
-    for (int s = 0; s < nseq; ++s) {
-        int len = cu[s + 1] - cu[s];
-        int nb = (len + block - 1) / block;
-        if (nb > R->n_max) R->n_max = nb;
-        R->row_offset[s + 1] = R->row_offset[s] + nb;
-    }
-    R->m_total = R->row_offset[nseq];
-    R->row_seq = (int *)malloc(sizeof(int) * (size_t)(R->m_total > 0 ? R->m_total : 1));
-    if (!R->row_seq) return -1;
-    for (int s = 0; s < nseq; ++s)
-        for (int r = R->row_offset[s]; r < R->row_offset[s + 1]; ++r) R->row_seq[r] = s;
-    return 0;
-}
 
 static void rows_free(rows_t *R) {
     free(R->row_offset);
+    free(R->kb_offset);
+    free(R->pb);
     free(R->row_seq);
+}
+
+static int rows_init(rows_t *R, int nseq, const int32_t *cu, const int32_t *cuk, int block) {
+    memset(R, 0, sizeof(*R));
+    R->nseq = nseq;
+    R->cuq = cu;
+    R->cuk = cuk ? cuk : cu;
+    R->row_offset = (int *)malloc(sizeof(int) * (size_t)(nseq + 1));
+    R->kb_offset = (int *)malloc(sizeof(int) * (size_t)(nseq + 1));
+    R->pb = (int *)malloc(sizeof(int) * (size_t)(nseq > 0 ? nseq : 1));
+    if (!R->row_offset || !R->kb_offset || !R->pb) return -1;
+    R->row_offset[0] = 0;
+    R->kb_offset[0] = 0;
+    for (int s = 0; s < nseq; ++s) {
+        int qlen = cu[s + 1] - cu[s];
+        int klen = R->cuk[s + 1] - R->cuk[s];
+        int prefix = klen - qlen;
+        if (qlen <= 0 || prefix < 0 || prefix % block != 0) {
+            rows_free(R);
+            return -1;
+        }
+        int nkb = (klen + block - 1) / block;
+        if (nkb > R->n_max) R->n_max = nkb;
+        R->pb[s] = prefix / block;
+        R->row_offset[s + 1] = R->row_offset[s] + (qlen + block - 1) / block;
+        R->kb_offset[s + 1] = R->kb_offset[s] + nkb;
+    }
+    R->m_total = R->row_offset[nseq];
+    R->kb_total = R->kb_offset[nseq];
+    R->row_seq = (int *)malloc(sizeof(int) * (size_t)(R->m_total > 0 ? R->m_total : 1));
+    if (!R->row_seq) {
+        rows_free(R);
+        return -1;
+    }
+    for (int s = 0; s < nseq; ++s)
+        for (int r = R->row_offset[s]; r < R->row_offset[s + 1]; ++r) R->row_seq[r] = s;
+    return 0;
 }
 
 int fpo_num_threads(void) {
@@ -74,10 +102,11 @@ int fpo_num_threads(void) {
 #endif
 }
 
-/* (m_total, n_max, row_offset[nseq+1]) of a packed batch. */
-int fpo_layout(int nseq, const int32_t *cu, int block, int32_t *m_total, int32_t *n_max, int32_t *row_offset) {
+/* (m_total, n_max, row_offset[nseq+1]) of a packed batch; -1 for lengths the path does not take. */
+int fpo_layout(int nseq, const int32_t *cu, const int32_t *cuk, int block, int32_t *m_total, int32_t *n_max,
+               int32_t *row_offset) {
     rows_t R;
-    if (rows_init(&R, nseq, cu, block)) return -1;
+    if (rows_init(&R, nseq, cu, cuk, block)) return -1;
     *m_total = R.m_total;
     *n_max = R.n_max;
     if (row_offset) memcpy(row_offset, R.row_offset, sizeof(int) * (size_t)(nseq + 1));
@@ -89,7 +118,8 @@ int fpo_layout(int nseq, const int32_t *cu, int block, int32_t *m_total, int32_t
  * Stage (i), pattern discovery: Sec. 3.1 (pooled keys), Sec. 3.2 Eq. 1-4, Alg. 1.
  *
  *   kbar_J   = mean of the keys of block J                       (Alg. 1 stage 1)
- *   x_i      = tau * q_i . kbar_J   for the queries i of tile I, J <= I
+ *   x_i      = tau * q_i . kbar_J   for the queries i of tile I, J <= I  (with a KV prefix of
+ *              PB blocks, "J <= I" reads "J <= I + PB" here and below)
  *   m_IJ     = max_i x_i ;  S_IJ = sum_i exp(x_i - m_IJ)          (Eq. 1, 2)
  *   M_I      = max_{J<=I} m_IJ ;  S'_IJ = S_IJ exp(m_IJ - M_I)    (Eq. 3)
  *   P_IJ     = S'_IJ / (sum_{K<=I} S'_IK + eps) ;  P_IJ = 0, J>I  (Eq. 4)
@@ -103,27 +133,28 @@ int fpo_layout(int nseq, const int32_t *cu, int block, int32_t *m_total, int32_t
  * rows: optional list of q-block rows to compute (all heads); NULL = all rows.
  * Rows not listed are left untouched; listed rows are written for all n_max columns.
  */
-int fpo_block_search(const uint16_t *Q, const uint16_t *K, int nseq, const int32_t *cu, int hq, int hkv, int d,
-                     int block, double tau, double eps, const int32_t *rows, int nrows, float *scores) {
+int fpo_block_search(const uint16_t *Q, const uint16_t *K, int nseq, const int32_t *cu, const int32_t *cuk, int hq,
+                     int hkv, int d, int block, double tau, double eps, const int32_t *rows, int nrows,
+                     float *scores) {
     rows_t R;
-    if (rows_init(&R, nseq, cu, block)) return -1;
+    if (rows_init(&R, nseq, cu, cuk, block)) return -1;
     const int g = hq / hkv;
     const size_t kb_stride = (size_t)hkv * d;
-    double *kbar = (double *)calloc((size_t)(R.m_total > 0 ? R.m_total : 1) * kb_stride, sizeof(double));
+    double *kbar = (double *)calloc((size_t)(R.kb_total > 0 ? R.kb_total : 1) * kb_stride, sizeof(double));
     if (!kbar) return -1;
 
     /* Alg. 1 stage 1: one mean vector per (key block, KV head). */
 #pragma omp parallel for schedule(static)
-    for (int r = 0; r < R.m_total; ++r) {
-        int s = R.row_seq[r];
-        int J = r - R.row_offset[s];
-        int t0 = cu[s] + J * block;
-        int t1 = t0 + block < cu[s + 1] ? t0 + block : cu[s + 1];
-        for (int hk = 0; hk < hkv; ++hk) {
-            double *kb = kbar + (size_t)r * kb_stride + (size_t)hk * d;
-            for (int t = t0; t < t1; ++t)
-                for (int c = 0; c < d; ++c) kb[c] += bf16_val(K[((size_t)t * hkv + hk) * d + c]);
-            for (int c = 0; c < d; ++c) kb[c] /= (double)(t1 - t0);
+    for (int s = 0; s < nseq; ++s) {
+        for (int J = 0; J < R.kb_offset[s + 1] - R.kb_offset[s]; ++J) {
+            int t0 = R.cuk[s] + J * block;
+            int t1 = t0 + block < R.cuk[s + 1] ? t0 + block : R.cuk[s + 1];
+            for (int hk = 0; hk < hkv; ++hk) {
+                double *kb = kbar + (size_t)(R.kb_offset[s] + J) * kb_stride + (size_t)hk * d;
+                for (int t = t0; t < t1; ++t)
+                    for (int c = 0; c < d; ++c) kb[c] += bf16_val(K[((size_t)t * hkv + hk) * d + c]);
+                for (int c = 0; c < d; ++c) kb[c] /= (double)(t1 - t0);
+            }
         }
     }
 
@@ -138,12 +169,13 @@ int fpo_block_search(const uint16_t *Q, const uint16_t *K, int nseq, const int32
             int r = rows ? rows[wk / hq] : (R.m_total - 1 - wk / hq);
             int h = wk % hq, hk = h / g;
             int s = R.row_seq[r];
-            int I = r - R.row_offset[s];
-            int t0 = cu[s] + I * block;
+            int Iq = r - R.row_offset[s];
+            int I = Iq + R.pb[s]; /* the tile's block index within its sequence */
+            int t0 = cu[s] + Iq * block;
             int nq = (t0 + block < cu[s + 1] ? t0 + block : cu[s + 1]) - t0;
             /* Alg. 1 stage 2: per block pair a max and a sum of exponentials over the query tile. */
             for (int J = 0; J <= I; ++J) {
-                const double *kb = kbar + (size_t)(R.row_offset[s] + J) * kb_stride + (size_t)hk * d;
+                const double *kb = kbar + (size_t)(R.kb_offset[s] + J) * kb_stride + (size_t)hk * d;
                 double mx = -INFINITY;
                 for (int i = 0; i < nq; ++i) {
                     const uint16_t *q = Q + ((size_t)(t0 + i) * hq + h) * d;
@@ -192,16 +224,16 @@ int fpo_block_search(const uint16_t *Q, const uint16_t *K, int nseq, const int32
  * paper's fill value is the block count); the boundary leaves them undefined.
  * The product alpha*max and the comparison are fp32, rounded once.
  */
-int fpo_threshold(const float *scores, int nseq, const int32_t *cu, int hq, int block, float alpha, int sink_tokens,
-                  int window_tokens, int32_t *idx, int32_t *cnt) {
+int fpo_threshold(const float *scores, int nseq, const int32_t *cu, const int32_t *cuk, int hq, int block,
+                  float alpha, int sink_tokens, int window_tokens, int32_t *idx, int32_t *cnt) {
     rows_t R;
-    if (rows_init(&R, nseq, cu, block)) return -1;
+    if (rows_init(&R, nseq, cu, cuk, block)) return -1;
     const int sinkB = (sink_tokens + block - 1) / block;
     const int winB = (window_tokens + block - 1) / block;
 #pragma omp parallel for schedule(dynamic, 16)
     for (int wk = 0; wk < R.m_total * hq; ++wk) {
         int r = wk / hq, h = wk % hq;
-        int I = r - R.row_offset[R.row_seq[r]];
+        int I = r - R.row_offset[R.row_seq[r]] + R.pb[R.row_seq[r]];
         const float *row = scores + ((size_t)h * R.m_total + r) * R.n_max;
         int32_t *out = idx + ((size_t)h * R.m_total + r) * R.n_max;
         float mx = row[0];
@@ -254,16 +286,17 @@ static void attend_row(const uint16_t *q, const uint16_t *K, const uint16_t *V, 
  * listed blocks that are not in the query's future, so the oracle is that definition:
  *
  *   O_t = sum_u softmax_u(tau q_t.k_u) v_u ,  u in listed blocks of (h, I(t)), u <= t
+ *   (positions within the sequence; with a KV prefix query t of the chunk is at P + t)
  *   lse_t = log2 sum_u 2^(tau log2e q_t.k_u)
  *
  * Query tile = block (the lists are indexed by the same I as the q-blocks).
  * rows: optional subset of q-block rows (all heads); NULL = all.  Unlisted rows untouched.
  */
-int fpo_sparse_prefill(const uint16_t *Q, const uint16_t *K, const uint16_t *V, int nseq, const int32_t *cu, int hq,
-                       int hkv, int d, int block, double tau, const int32_t *idx, const int32_t *cnt,
-                       const int32_t *rows, int nrows, float *O, float *lse) {
+int fpo_sparse_prefill(const uint16_t *Q, const uint16_t *K, const uint16_t *V, int nseq, const int32_t *cu,
+                       const int32_t *cuk, int hq, int hkv, int d, int block, double tau, const int32_t *idx,
+                       const int32_t *cnt, const int32_t *rows, int nrows, float *O, float *lse) {
     rows_t R;
-    if (rows_init(&R, nseq, cu, block)) return -1;
+    if (rows_init(&R, nseq, cu, cuk, block)) return -1;
     const int g = hq / hkv;
     int T = cu[nseq];
     const int nwork = (rows ? nrows : R.m_total) * hq;
@@ -282,11 +315,12 @@ int fpo_sparse_prefill(const uint16_t *Q, const uint16_t *K, const uint16_t *V, 
             const int32_t *list = idx + ((size_t)h * R.m_total + r) * R.n_max;
             int c = cnt[(size_t)h * R.m_total + r];
             for (int t = t0; t < t1; ++t) {
+                int pos = R.pb[s] * block + (t - cu[s]); /* the query's position in its sequence */
                 int nk = 0;
                 for (int n = 0; n < c; ++n) {
-                    int u0 = cu[s] + list[n] * block;
-                    for (int u = u0; u < u0 + block && u < cu[s + 1]; ++u)
-                        if (u <= t) keys[nk++] = u;
+                    int p0 = list[n] * block;
+                    for (int p = p0; p < p0 + block && R.cuk[s] + p < R.cuk[s + 1]; ++p)
+                        if (p <= pos) keys[nk++] = R.cuk[s] + p;
                 }
                 attend_row(Q + ((size_t)t * hq + h) * d, K, V, hkv, hk, d, tau, keys, nk, logit,
                            O + ((size_t)t * hq + h) * d, lse ? lse + (size_t)h * T + t : NULL);
@@ -301,12 +335,13 @@ int fpo_sparse_prefill(const uint16_t *Q, const uint16_t *K, const uint16_t *V, 
 
 /*
  * Full causal attention (the comparison the paper measures against):
- *   O_t = sum_{u<=t, same sequence} softmax_u(tau q_t.k_u) v_u.
+ *   O_t = sum_{u<=t, same sequence} softmax_u(tau q_t.k_u) v_u  (u, t: positions in the sequence).
  */
-int fpo_dense_prefill(const uint16_t *Q, const uint16_t *K, const uint16_t *V, int nseq, const int32_t *cu, int hq,
-                      int hkv, int d, int block, double tau, const int32_t *rows, int nrows, float *O, float *lse) {
+int fpo_dense_prefill(const uint16_t *Q, const uint16_t *K, const uint16_t *V, int nseq, const int32_t *cu,
+                      const int32_t *cuk, int hq, int hkv, int d, int block, double tau, const int32_t *rows, int nrows,
+                      float *O, float *lse) {
     rows_t R;
-    if (rows_init(&R, nseq, cu, block)) return -1;
+    if (rows_init(&R, nseq, cu, cuk, block)) return -1;
     const int g = hq / hkv;
     int T = cu[nseq];
     const int nwork = (rows ? nrows : R.m_total) * hq;
@@ -323,8 +358,9 @@ int fpo_dense_prefill(const uint16_t *Q, const uint16_t *K, const uint16_t *V, i
             int t0 = cu[s] + I * block;
             int t1 = t0 + block < cu[s + 1] ? t0 + block : cu[s + 1];
             for (int t = t0; t < t1; ++t) {
+                int pos = R.pb[s] * block + (t - cu[s]);
                 int nk = 0;
-                for (int u = cu[s]; u <= t; ++u) keys[nk++] = u;
+                for (int p = 0; p <= pos; ++p) keys[nk++] = R.cuk[s] + p;
                 attend_row(Q + ((size_t)t * hq + h) * d, K, V, hkv, hk, d, tau, keys, nk, logit,
                            O + ((size_t)t * hq + h) * d, lse ? lse + (size_t)h * T + t : NULL);
             }
