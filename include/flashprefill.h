@@ -14,13 +14,20 @@
  *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library never
  *     frees or reallocates it.  `cu_seqlens` inside fp_shape is a HOST pointer, read only
  *     during fp_layout / fp_plan_create.
- *   - Q and O are [T, Hq, d], K and V are [T, Hkv, d], bf16, contiguous, token-major;
- *     T = cu_seqlens[nseq].  Sequence s owns tokens cu_seqlens[s] .. cu_seqlens[s+1]-1.
+ *   - Q and O are [T, Hq, d], K and V are [Tk, Hkv, d], bf16, contiguous, token-major;
+ *     T = cu_seqlens[nseq], Tk = cu_seqlens_k[nseq].  Sequence s owns query tokens
+ *     cu_seqlens[s] .. cu_seqlens[s+1]-1 and key tokens cu_seqlens_k[s] .. cu_seqlens_k[s+1]-1.
  *     Query head h reads KV head h / (Hq / Hkv).
+ *   - Plain prefill: cu_seqlens_k == NULL, keys and queries are the same tokens.  Chunked
+ *     prefill (the queries are the last q_len tokens of a sequence whose first kv_len - q_len
+ *     keys were produced earlier): query i of the chunk sits at position prefix + i and sees
+ *     keys 0 .. prefix + i; prefix = kv_len - q_len must be a multiple of `block`.
  *   - Blocks of `block` (=128) tokens are aligned to the start of each sequence; a sequence
- *     of length L has ceil(L / block) blocks, the last one possibly partial.  Query-block
- *     row r = row_offset[s] + I addresses q-block I of sequence s; m_total = total rows,
- *     n_max = most blocks in any one sequence.
+ *     of kv_len keys has ceil(kv_len / block) key blocks, the last one possibly partial.
+ *     Query-block row r = row_offset[s] + I addresses q-block I of sequence s's chunk, which
+ *     is block I + prefix / block of the sequence: wherever a comment below says "J <= I",
+ *     I is that index within the sequence.  m_total = total rows, n_max = most key blocks
+ *     in any one sequence.
  *   - scores: fp32 [Hq, m_total, n_max]; idx: int32 [Hq, m_total, n_max]; cnt: int32
  *     [Hq, m_total]; lse: fp32 [Hq, T].  Head-major so that one row is contiguous (the
  *     paper's Alg. 2 indexes [batch, q-block, k-block, head]).
@@ -43,7 +50,8 @@ extern "C" {
 typedef enum {
     FP_OK = 0,
     FP_ERR_INVALID_ARG = 1, /* null pointer, inconsistent shape, bad cu_seqlens            */
-    FP_ERR_UNSUPPORTED = 2, /* head_dim != 128, block != 128, or more than 4096 blocks/seq  */
+    FP_ERR_UNSUPPORTED = 2, /* head_dim != 128, block != 128, more than 4096 blocks/seq, or a */
+                            /* KV prefix that is not a multiple of the block                */
     FP_ERR_DEVICE = 3,      /* HIP runtime error (no device, allocation or launch failure) */
     FP_ERR_NOMEM = 4        /* host allocation failed                                      */
 } fp_status;
@@ -55,6 +63,8 @@ typedef struct {
     int32_t head_dim;          /* 128                                                         */
     int32_t block;             /* 128 (Appendix A: uniform block size)                        */
     float scale;               /* softmax scale tau; <= 0 selects 1/sqrt(head_dim)            */
+    const int32_t *cu_seqlens_k; /* HOST, nseq+1 entries, or NULL (= cu_seqlens): key-side      */
+                               /* lengths for chunked prefill, kv_len >= q_len per sequence   */
 } fp_shape;
 
 typedef struct {
@@ -73,7 +83,7 @@ const char *fp_status_string(fp_status s);
 fp_status fp_layout(const fp_shape *shape, int32_t *m_total, int32_t *n_max, int32_t *row_offset);
 
 /* Validates `shape`, selects `device`, allocates and fills the plan's device tables and its
- * workspace (pooled keys: 2 x m_total x Hkv x 128 bf16).  Synchronous.  The plan is immutable
+ * workspace (pooled keys: 2 x (key blocks) x Hkv x 128 bf16).  Synchronous.  The plan is immutable
  * afterwards and may be used for any number of calls; destroy it with fp_plan_destroy after
  * the work enqueued with it has finished. */
 fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **plan);

@@ -23,7 +23,8 @@ EXPORTS = ("fp_status_string", "fp_layout", "fp_plan_create", "fp_plan_destroy",
 class fp_shape(ctypes.Structure):
     _fields_ = [("nseq", ctypes.c_int32), ("cu_seqlens", ctypes.POINTER(ctypes.c_int32)),
                 ("hq", ctypes.c_int32), ("hkv", ctypes.c_int32), ("head_dim", ctypes.c_int32),
-                ("block", ctypes.c_int32), ("scale", ctypes.c_float)]
+                ("block", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("cu_seqlens_k", ctypes.POINTER(ctypes.c_int32))]
 
 
 class fp_params(ctypes.Structure):
@@ -73,18 +74,22 @@ def _check(status: int, where: str) -> None:
 
 
 def make_shape(cu_seqlens: Sequence[int], hq: int, hkv: int, head_dim: int = 128, block: int = 128,
-               scale: float = 0.0):
-    """Builds an fp_shape; returns (shape, keepalive) where keepalive owns the host cu_seqlens."""
+               scale: float = 0.0, cu_seqlens_k: Optional[Sequence[int]] = None):
+    """Builds an fp_shape; returns (shape, keepalive) where keepalive owns the host arrays."""
+    i32p = ctypes.POINTER(ctypes.c_int32)
     cu = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
-    s = fp_shape(int(cu.size - 1), cu.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), hq, hkv, head_dim, block,
-                 float(scale))
-    return s, cu
+    ck = None if cu_seqlens_k is None else np.ascontiguousarray(cu_seqlens_k, dtype=np.int32)
+    if ck is not None and ck.size != cu.size:
+        raise ValueError("cu_seqlens_k must have as many entries as cu_seqlens")
+    s = fp_shape(int(cu.size - 1), cu.ctypes.data_as(i32p), hq, hkv, head_dim, block, float(scale),
+                 None if ck is None else ck.ctypes.data_as(i32p))
+    return s, (cu, ck)
 
 
 def fp_layout(cu_seqlens: Sequence[int], hq: int, hkv: int, head_dim: int = 128, block: int = 128,
-              scale: float = 0.0):
+              scale: float = 0.0, cu_seqlens_k: Optional[Sequence[int]] = None):
     """Host-only shape check; returns (m_total, n_max, row_offset)."""
-    s, keep = make_shape(cu_seqlens, hq, hkv, head_dim, block, scale)
+    s, keep = make_shape(cu_seqlens, hq, hkv, head_dim, block, scale, cu_seqlens_k)
     m, n = ctypes.c_int32(), ctypes.c_int32()
     ro = np.zeros(max(int(s.nseq) + 1, 1), np.int32)
     _check(lib().fp_layout(ctypes.byref(s), ctypes.byref(m), ctypes.byref(n), ro.ctypes.data_as(ctypes.c_void_p)),
@@ -113,13 +118,16 @@ class Plan:
     """Owns an fp_plan (device tables + pooled-key workspace) for one packed-batch shape."""
 
     def __init__(self, cu_seqlens: Sequence[int], hq: int, hkv: int, head_dim: int = 128, block: int = 128,
-                 scale: float = 0.0, device: int = 0):
+                 scale: float = 0.0, device: int = 0, cu_seqlens_k: Optional[Sequence[int]] = None):
         self.cu_seqlens = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
+        self.cu_seqlens_k = None if cu_seqlens_k is None else np.ascontiguousarray(cu_seqlens_k, dtype=np.int32)
         self.hq, self.hkv, self.head_dim, self.block = hq, hkv, head_dim, block
         self.device = device
-        self.m_total, self.n_max, self.row_offset = fp_layout(self.cu_seqlens, hq, hkv, head_dim, block, scale)
-        self.T = int(self.cu_seqlens[-1])
-        s, keep = make_shape(self.cu_seqlens, hq, hkv, head_dim, block, scale)
+        self.m_total, self.n_max, self.row_offset = fp_layout(self.cu_seqlens, hq, hkv, head_dim, block, scale,
+                                                              self.cu_seqlens_k)
+        self.T = int(self.cu_seqlens[-1])                                                   # query tokens
+        self.Tk = self.T if self.cu_seqlens_k is None else int(self.cu_seqlens_k[-1])      # key tokens
+        s, keep = make_shape(self.cu_seqlens, hq, hkv, head_dim, block, scale, self.cu_seqlens_k)
         h = ctypes.c_void_p()
         _check(lib().fp_plan_create(ctypes.byref(s), device, ctypes.byref(h)), "fp_plan_create")
         self._h = h
@@ -139,7 +147,7 @@ class Plan:
     def fp_block_search(self, Q, K, scores=None, eps: float = 1e-10, stream=None):
         import torch
         q = _dev_ptr(Q, torch.bfloat16, (self.T, self.hq, self.head_dim), "Q")
-        k = _dev_ptr(K, torch.bfloat16, (self.T, self.hkv, self.head_dim), "K")
+        k = _dev_ptr(K, torch.bfloat16, (self.Tk, self.hkv, self.head_dim), "K")
         if scores is None:
             scores = torch.empty((self.hq, self.m_total, self.n_max), dtype=torch.float32, device=Q.device)
         s = _dev_ptr(scores, torch.float32, (self.hq, self.m_total, self.n_max), "scores")
@@ -164,7 +172,7 @@ class Plan:
                          cnt=None, eps: float = 1e-10, stream=None):
         import torch
         q = _dev_ptr(Q, torch.bfloat16, (self.T, self.hq, self.head_dim), "Q")
-        k = _dev_ptr(K, torch.bfloat16, (self.T, self.hkv, self.head_dim), "K")
+        k = _dev_ptr(K, torch.bfloat16, (self.Tk, self.hkv, self.head_dim), "K")
         if idx is None:
             idx = torch.empty((self.hq, self.m_total, self.n_max), dtype=torch.int32, device=Q.device)
         if cnt is None:
@@ -179,8 +187,8 @@ class Plan:
     def _qkv(self, Q, K, V):
         import torch
         return (_dev_ptr(Q, torch.bfloat16, (self.T, self.hq, self.head_dim), "Q"),
-                _dev_ptr(K, torch.bfloat16, (self.T, self.hkv, self.head_dim), "K"),
-                _dev_ptr(V, torch.bfloat16, (self.T, self.hkv, self.head_dim), "V"))
+                _dev_ptr(K, torch.bfloat16, (self.Tk, self.hkv, self.head_dim), "K"),
+                _dev_ptr(V, torch.bfloat16, (self.Tk, self.hkv, self.head_dim), "V"))
 
     def fp_sparse_prefill(self, Q, K, V, idx, cnt, O=None, lse=None, want_lse: bool = True, stream=None):
         import torch

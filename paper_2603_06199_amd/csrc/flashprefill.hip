@@ -21,29 +21,40 @@ namespace {
 constexpr int kMaxBlocksPerSeq = 4096;
 
 struct Layout {
-    int m_total = 0, n_max = 0;
-    std::vector<int32_t> row_offset;
+    int m_total = 0, n_max = 0, kb_total = 0;
+    std::vector<int32_t> row_offset;   // first q-block row of each sequence
+    std::vector<int32_t> kb_offset;    // first key block of each sequence among all key blocks
+    std::vector<int32_t> prefix_blocks;
 };
 
 fp_status check_shape(const fp_shape *s, Layout *out) {
     if (s == nullptr || s->cu_seqlens == nullptr) return FP_ERR_INVALID_ARG;
     if (s->nseq < 1 || s->hq < 1 || s->hkv < 1 || s->hq % s->hkv != 0) return FP_ERR_INVALID_ARG;
-    if (s->cu_seqlens[0] != 0) return FP_ERR_INVALID_ARG;
+    const int32_t *cuk = s->cu_seqlens_k ? s->cu_seqlens_k : s->cu_seqlens;
+    if (s->cu_seqlens[0] != 0 || cuk[0] != 0) return FP_ERR_INVALID_ARG;
     for (int i = 0; i < s->nseq; ++i)
-        if (s->cu_seqlens[i + 1] <= s->cu_seqlens[i]) return FP_ERR_INVALID_ARG;
+        if (s->cu_seqlens[i + 1] <= s->cu_seqlens[i] || cuk[i + 1] <= cuk[i]) return FP_ERR_INVALID_ARG;
     if (!(s->scale == s->scale) || std::isinf(s->scale)) return FP_ERR_INVALID_ARG;
     if (s->head_dim != fp::kHeadDim || s->block != fp::kBlock) return FP_ERR_UNSUPPORTED;
     Layout L;
-    L.row_offset.resize((size_t)s->nseq + 1);
-    L.row_offset[0] = 0;
+    L.row_offset.assign((size_t)s->nseq + 1, 0);
+    L.kb_offset.assign((size_t)s->nseq + 1, 0);
+    L.prefix_blocks.assign((size_t)s->nseq, 0);
     for (int i = 0; i < s->nseq; ++i) {
-        const int64_t len = (int64_t)s->cu_seqlens[i + 1] - s->cu_seqlens[i];
-        const int64_t nb = (len + s->block - 1) / s->block;
-        if (nb > kMaxBlocksPerSeq) return FP_ERR_UNSUPPORTED;
-        L.n_max = std::max<int>(L.n_max, (int)nb);
-        L.row_offset[i + 1] = L.row_offset[i] + (int32_t)nb;
+        const int64_t qlen = (int64_t)s->cu_seqlens[i + 1] - s->cu_seqlens[i];
+        const int64_t klen = (int64_t)cuk[i + 1] - cuk[i];
+        const int64_t prefix = klen - qlen;
+        if (prefix < 0) return FP_ERR_INVALID_ARG;
+        if (prefix % s->block != 0) return FP_ERR_UNSUPPORTED;
+        const int64_t nkb = (klen + s->block - 1) / s->block;
+        if (nkb > kMaxBlocksPerSeq) return FP_ERR_UNSUPPORTED;
+        L.n_max = std::max<int>(L.n_max, (int)nkb);
+        L.prefix_blocks[i] = (int32_t)(prefix / s->block);
+        L.row_offset[i + 1] = L.row_offset[i] + (int32_t)((qlen + s->block - 1) / s->block);
+        L.kb_offset[i + 1] = L.kb_offset[i] + (int32_t)nkb;
     }
     L.m_total = L.row_offset[s->nseq];
+    L.kb_total = L.kb_offset[s->nseq];
     if (out) *out = std::move(L);
     return FP_OK;
 }
@@ -52,13 +63,14 @@ fp_status check_shape(const fp_shape *s, Layout *out) {
 
 struct fp_plan {
     int device = 0;
-    int nseq = 0, hq = 0, hkv = 0, g = 0, T = 0;
-    int m_total = 0, n_max = 0;
+    int nseq = 0, hq = 0, hkv = 0, g = 0, T = 0;   // T: query tokens
+    int m_total = 0, n_max = 0, kb_total = 0;
     float c = 0.f;                    // tau * log2(e)
-    fp::BlockRec *d_blk = nullptr;    // [m_total]
-    int32_t *d_order = nullptr;       // [m_total] rows, largest I first
-    fp::BlockRec *d_blk_ranked = nullptr;   // [m_total] d_blk permuted by d_order
-    uint16_t *d_kb_hi = nullptr;      // [m_total, hkv, 128] bf16
+    fp::RowRec *d_rows = nullptr;     // [m_total]
+    int32_t *d_order = nullptr;       // [m_total] rows, most causal key blocks first
+    fp::RowRec *d_rows_ranked = nullptr;   // [m_total] d_rows permuted by d_order
+    fp::KeyBlockRec *d_kblk = nullptr;     // [kb_total]
+    uint16_t *d_kb_hi = nullptr;      // [kb_total, hkv, 128] bf16
     uint16_t *d_kb_lo = nullptr;
     size_t search_lds = 0;
     int n_pad = 0;
@@ -92,9 +104,10 @@ void fp_plan_destroy(fp_plan *p) {
     int prev = 0;
     const bool have_prev = hipGetDevice(&prev) == hipSuccess;
     if (hipSetDevice(p->device) == hipSuccess) {
-        if (p->d_blk) (void)hipFree(p->d_blk);
+        if (p->d_rows) (void)hipFree(p->d_rows);
         if (p->d_order) (void)hipFree(p->d_order);
-        if (p->d_blk_ranked) (void)hipFree(p->d_blk_ranked);
+        if (p->d_rows_ranked) (void)hipFree(p->d_rows_ranked);
+        if (p->d_kblk) (void)hipFree(p->d_kblk);
         if (p->d_kb_hi) (void)hipFree(p->d_kb_hi);
         if (p->d_kb_lo) (void)hipFree(p->d_kb_lo);
     }
@@ -121,41 +134,58 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
     p->T = shape->cu_seqlens[shape->nseq];
     p->m_total = L.m_total;
     p->n_max = L.n_max;
+    p->kb_total = L.kb_total;
     const float tau = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
     p->c = tau * fp::kLog2e;
     p->n_pad = (L.n_max + 31) / 32 * 32;
     p->search_lds = (size_t)fp::kSearchStageBytes + fp::kSearchRowHeader + (size_t)fp::kSearchHeads * p->n_pad * sizeof(float);
 
-    std::vector<fp::BlockRec> blk((size_t)L.m_total);
+    const int32_t *cuk = shape->cu_seqlens_k ? shape->cu_seqlens_k : shape->cu_seqlens;
+    std::vector<fp::RowRec> rows((size_t)L.m_total);
+    std::vector<fp::KeyBlockRec> kblk((size_t)L.kb_total);
     for (int s = 0; s < shape->nseq; ++s) {
         const int a = shape->cu_seqlens[s], b = shape->cu_seqlens[s + 1];
         for (int r = L.row_offset[s]; r < L.row_offset[s + 1]; ++r) {
-            const int I = r - L.row_offset[s];
-            const int t0 = a + I * fp::kBlock;
-            blk[(size_t)r] = make_int4(t0, std::min(fp::kBlock, b - t0), L.row_offset[s], b);
+            const int Iq = r - L.row_offset[s];
+            const int t0 = a + Iq * fp::kBlock;
+            fp::RowRec rec;
+            rec.q_tok0 = t0;
+            rec.q_len = std::min(fp::kBlock, b - t0);
+            rec.I = Iq + L.prefix_blocks[s];
+            rec.kb_row0 = L.kb_offset[s];
+            rec.k_tok0 = cuk[s];
+            rec.k_end = cuk[s + 1];
+            rec.pad0 = rec.pad1 = 0;
+            rows[(size_t)r] = rec;
+        }
+        for (int j = L.kb_offset[s]; j < L.kb_offset[s + 1]; ++j) {
+            const int t0 = cuk[s] + (j - L.kb_offset[s]) * fp::kBlock;
+            kblk[(size_t)j] = make_int2(t0, std::min(fp::kBlock, cuk[s + 1] - t0));
         }
     }
-    // Heaviest rows first: a row's work grows with its block index I within its sequence.
+    // Heaviest rows first: a row's work grows with the number of its causal key blocks.
     std::vector<int32_t> order((size_t)L.m_total);
     std::iota(order.begin(), order.end(), 0);
     std::stable_sort(order.begin(), order.end(),
-                     [&](int32_t x, int32_t y) { return x - blk[(size_t)x].z > y - blk[(size_t)y].z; });
+                     [&](int32_t x, int32_t y) { return rows[(size_t)x].I > rows[(size_t)y].I; });
 
-    std::vector<fp::BlockRec> blk_ranked((size_t)L.m_total);
-    for (int i = 0; i < L.m_total; ++i) blk_ranked[(size_t)i] = blk[(size_t)order[(size_t)i]];
+    std::vector<fp::RowRec> rows_ranked((size_t)L.m_total);
+    for (int i = 0; i < L.m_total; ++i) rows_ranked[(size_t)i] = rows[(size_t)order[(size_t)i]];
 
     int prev = 0;
     (void)hipGetDevice(&prev);
     bool ok = hipSetDevice(device) == hipSuccess;
-    const size_t kb_bytes = (size_t)L.m_total * p->hkv * fp::kHeadDim * sizeof(uint16_t);
-    ok = ok && hipMalloc(&p->d_blk, blk.size() * sizeof(fp::BlockRec)) == hipSuccess;
+    const size_t kb_bytes = (size_t)L.kb_total * p->hkv * fp::kHeadDim * sizeof(uint16_t);
+    ok = ok && hipMalloc(&p->d_rows, rows.size() * sizeof(fp::RowRec)) == hipSuccess;
     ok = ok && hipMalloc(&p->d_order, order.size() * sizeof(int32_t)) == hipSuccess;
-    ok = ok && hipMalloc(&p->d_blk_ranked, blk.size() * sizeof(fp::BlockRec)) == hipSuccess;
+    ok = ok && hipMalloc(&p->d_rows_ranked, rows.size() * sizeof(fp::RowRec)) == hipSuccess;
+    ok = ok && hipMalloc(&p->d_kblk, kblk.size() * sizeof(fp::KeyBlockRec)) == hipSuccess;
     ok = ok && hipMalloc(&p->d_kb_hi, kb_bytes) == hipSuccess;
     ok = ok && hipMalloc(&p->d_kb_lo, kb_bytes) == hipSuccess;
-    ok = ok && hipMemcpy(p->d_blk, blk.data(), blk.size() * sizeof(fp::BlockRec), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(p->d_rows, rows.data(), rows.size() * sizeof(fp::RowRec), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(p->d_kblk, kblk.data(), kblk.size() * sizeof(fp::KeyBlockRec), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_order, order.data(), order.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
-    ok = ok && hipMemcpy(p->d_blk_ranked, blk_ranked.data(), blk.size() * sizeof(fp::BlockRec), hipMemcpyHostToDevice) == hipSuccess;
+    ok = ok && hipMemcpy(p->d_rows_ranked, rows_ranked.data(), rows.size() * sizeof(fp::RowRec), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<true>),
@@ -192,17 +222,17 @@ static fp_status launch_search(fp_plan *p, const void *Q, const void *K, float e
                                const fp::SelectArgs *sel, void *hip_stream) {
     if (!on_plan_device(p)) return FP_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    fp::pool_k_kernel<<<dim3(p->m_total, p->hkv), 256, 0, st>>>(static_cast<const uint16_t *>(K), p->d_blk, p->hkv,
-                                                                 p->d_kb_hi, p->d_kb_lo);
+    fp::pool_k_kernel<<<dim3(p->kb_total, p->hkv), 256, 0, st>>>(static_cast<const uint16_t *>(K), p->d_kblk, p->hkv,
+                                                                  p->d_kb_hi, p->d_kb_lo);
     const int nchunk = (p->g + fp::kSearchHeads - 1) / fp::kSearchHeads;
     const dim3 grid(p->m_total * p->hkv * nchunk);
     const uint16_t *q = static_cast<const uint16_t *>(Q);
     if (sel != nullptr)
-        fp::search_kernel<true><<<grid, 256, p->search_lds, st>>>(q, p->d_kb_hi, p->d_kb_lo, p->d_blk_ranked, p->d_order,
+        fp::search_kernel<true><<<grid, 256, p->search_lds, st>>>(q, p->d_kb_hi, p->d_kb_lo, p->d_rows_ranked, p->d_order,
                                                                   p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
                                                                   p->c, eps, nullptr, *sel);
     else
-        fp::search_kernel<false><<<grid, 256, p->search_lds, st>>>(q, p->d_kb_hi, p->d_kb_lo, p->d_blk_ranked, p->d_order,
+        fp::search_kernel<false><<<grid, 256, p->search_lds, st>>>(q, p->d_kb_hi, p->d_kb_lo, p->d_rows_ranked, p->d_order,
                                                                    p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
                                                                    p->c, eps, scores, fp::SelectArgs{});
     return launch_status();
@@ -243,10 +273,10 @@ fp_status fp_threshold(fp_plan *p, const float *scores, const fp_params *params,
     const size_t lds = (size_t)fp::kThresholdWaves * n_pad * sizeof(float);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     if (p->n_max % 4 == 0 && reinterpret_cast<uintptr_t>(scores) % 16 == 0)
-        fp::threshold_kernel<true><<<grid, 64 * fp::kThresholdWaves, lds, st>>>(scores, p->d_blk, p->m_total, p->n_max, n_pad, p->hq,
+        fp::threshold_kernel<true><<<grid, 64 * fp::kThresholdWaves, lds, st>>>(scores, p->d_rows, p->m_total, p->n_max, n_pad, p->hq,
                                                                                params->alpha, sinkB, winB, idx, cnt);
     else
-        fp::threshold_kernel<false><<<grid, 64 * fp::kThresholdWaves, lds, st>>>(scores, p->d_blk, p->m_total, p->n_max, n_pad, p->hq,
+        fp::threshold_kernel<false><<<grid, 64 * fp::kThresholdWaves, lds, st>>>(scores, p->d_rows, p->m_total, p->n_max, n_pad, p->hq,
                                                                                 params->alpha, sinkB, winB, idx, cnt);
     return launch_status();
 }
@@ -261,10 +291,10 @@ static fp_status launch_attn(fp_plan *p, bool sparse, const void *Q, const void 
                    *v = static_cast<const uint16_t *>(V);
     uint16_t *o = static_cast<uint16_t *>(O);
     if (sparse)
-        fp::attn_kernel<true><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, idx, cnt, p->d_blk_ranked, p->d_order, p->m_total, p->n_max,
+        fp::attn_kernel<true><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, idx, cnt, p->d_rows_ranked, p->d_order, p->m_total, p->n_max,
                                                            p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     else
-        fp::attn_kernel<false><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, nullptr, nullptr, p->d_blk_ranked, p->d_order, p->m_total,
+        fp::attn_kernel<false><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, nullptr, nullptr, p->d_rows_ranked, p->d_order, p->m_total,
                                                             p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     return launch_status();
 }

@@ -163,7 +163,7 @@ __device__ __forceinline__ void attn_pv(const char *smem, const uint32_t (&vaddr
 template <bool SPARSE>
 __global__ __launch_bounds__(256, 2) void attn_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
-    const int32_t *__restrict__ idx, const int32_t *__restrict__ cnt, const BlockRec *__restrict__ blk_ranked,
+    const int32_t *__restrict__ idx, const int32_t *__restrict__ cnt, const RowRec *__restrict__ rows_ranked,
     const int32_t *__restrict__ order, int m_total, int n_max, int hq, int hkv, int g, int T, float c,
     uint16_t *__restrict__ O, float *__restrict__ lse) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -173,11 +173,11 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     if (s >= m_total * hkv) return;
     const int rank = s / hkv, hk = s - rank * hkv;
     const int r = order[rank];               // both tables are indexed by rank: one round trip
-    const BlockRec bi = blk_ranked[rank];
+    const RowRec bi = rows_ranked[rank];
     const int h = hk * g + hg;
-    const int I = r - bi.z;
-    const int seq_tok0 = bi.x - I * kBlock;
-    const int last_tok = bi.w - 1;
+    const int I = bi.I;                  // diagonal key block (q-block index + KV prefix blocks)
+    const int seq_tok0 = bi.k_tok0;      // K/V tokens of the sequence: seq_tok0 .. last_tok
+    const int last_tok = bi.k_end - 1;
 
     const int tid = threadIdx.x, l = tid & 63, half = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, held in a scalar register
@@ -199,12 +199,12 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     const int ntiles = 2 * nb;
 
     if (ntiles == 0) {   // empty list: O = 0, lse = -inf (uniform exit, before any barrier)
-        if (q_local < bi.y) {
-            uint16_t *op = O + ((size_t)(bi.x + q_local) * hq + h) * kHeadDim + 64 * half;
+        if (q_local < bi.q_len) {
+            uint16_t *op = O + ((size_t)(bi.q_tok0 + q_local) * hq + h) * kHeadDim + 64 * half;
             const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4 *>(op + 8 * i) = z;
-            if (lse != nullptr && half == 0) lse[(size_t)h * T + bi.x + q_local] = -INFINITY;
+            if (lse != nullptr && half == 0) lse[(size_t)h * T + bi.q_tok0 + q_local] = -INFINITY;
         }
         return;
     }
@@ -217,8 +217,8 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     // with the exact count, for the fragments and the first K tile together.
     bf16x8 qb[8];
     {
-        int row = q_local < bi.y ? q_local : bi.y - 1;
-        const uint16_t *qp = Q + ((size_t)(bi.x + row) * hq + h) * kHeadDim + 8 * half;
+        int row = q_local < bi.q_len ? q_local : bi.q_len - 1;
+        const uint16_t *qp = Q + ((size_t)(bi.q_tok0 + row) * hq + h) * kHeadDim + 8 * half;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
             asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=&v"(qb[ks]) : "v"(qp), "n"(32 * ks) : "memory");
@@ -406,12 +406,12 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
         for (int i = 0; i < 8; ++i) {
             const int orow = 4 * i + (l >> 4);
             const u32x4 v = *reinterpret_cast<const u32x4 *>(ob + orow * kAttnRowBytes + (pc << 4));
-            if (32 * w + orow < bi.y)
-                *reinterpret_cast<u32x4 *>(O + ((size_t)(bi.x + 32 * w + orow) * hq + h) * kHeadDim + ((pc ^ (orow & 15)) << 3)) = v;
+            if (32 * w + orow < bi.q_len)
+                *reinterpret_cast<u32x4 *>(O + ((size_t)(bi.q_tok0 + 32 * w + orow) * hq + h) * kHeadDim + ((pc ^ (orow & 15)) << 3)) = v;
         }
     }
-    if (q_local < bi.y && lse != nullptr && half == 0)
-        lse[(size_t)h * T + bi.x + q_local] = l_tot > 0.f ? m_run * c + __log2f(l_tot) : -INFINITY;
+    if (q_local < bi.q_len && lse != nullptr && half == 0)
+        lse[(size_t)h * T + bi.q_tok0 + q_local] = l_tot > 0.f ? m_run * c + __log2f(l_tot) : -INFINITY;
 #undef FP_TILE_BLOCK
 #undef FP_LOAD
 #undef FP_LOAD_FULL

@@ -18,9 +18,17 @@ constexpr int kBlock = 128;    // tokens per block (Appendix A)
 constexpr int kHeadDim = 128;
 constexpr float kLog2e = 1.4426950408889634f;
 
-// Per block-row record: x = first token of the block, y = valid tokens in it (1..128),
-// z = first row of its sequence, w = one past the last token of its sequence.
-typedef int4 BlockRec;
+// One q-block row.  Queries: first token of the block (index into Q and O) and the number of
+// valid tokens in it (1..128).  I = the block's index within its sequence, i.e. its index within
+// the query chunk plus the KV prefix in blocks; its causal key blocks are J <= I.  Keys: the
+// sequence's first token (index into K and V), one past its last, and the first row of its pooled
+// keys in the workspace.
+struct __attribute__((aligned(16))) RowRec {
+    int q_tok0, q_len, I, kb_row0;
+    int k_tok0, k_end, pad0, pad1;
+};
+// One key block: first token and number of valid tokens.
+typedef int2 KeyBlockRec;
 
 #define FP_LDS(T) __attribute__((address_space(3))) T
 

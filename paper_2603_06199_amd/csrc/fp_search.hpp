@@ -11,12 +11,12 @@ namespace fp {
 // The mean is stored as two bf16 planes, hi = bf16(mean) and lo = bf16(mean - hi), so that the
 // score kernel can feed it to bf16 MFMA twice and keep ~16 mantissa bits of the pooled key.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict__ K, const BlockRec *__restrict__ blk,
-                                                     int hkv, uint16_t *__restrict__ kb_hi,
-                                                     uint16_t *__restrict__ kb_lo) {
+__global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict__ K,
+                                                     const KeyBlockRec *__restrict__ kblk, int hkv,
+                                                     uint16_t *__restrict__ kb_hi, uint16_t *__restrict__ kb_lo) {
     __shared__ float red[16][kHeadDim + 4];
     const int r = blockIdx.x, hk = blockIdx.y;
-    const BlockRec bi = blk[r];
+    const KeyBlockRec bi = kblk[r];
     const int t = threadIdx.x, chunk = t & 15, rg = t >> 4;
     float acc[8];
 #pragma unroll
@@ -140,7 +140,7 @@ struct SelectArgs {
 template <bool SELECT>
 __global__ __launch_bounds__(256, 4) void search_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ kb_hi, const uint16_t *__restrict__ kb_lo,
-    const BlockRec *__restrict__ blk_ranked, const int32_t *__restrict__ order, int m_total, int n_max, int n_pad,
+    const RowRec *__restrict__ rows_ranked, const int32_t *__restrict__ order, int m_total, int n_max, int n_pad,
     int hq, int hkv, int g, int nchunk, float c /* tau*log2(e) */, float eps, float *__restrict__ scores,
     SelectArgs sel) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -153,8 +153,8 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     const int rem = blockIdx.x - rank * per_row;
     const int hk = rem / nchunk, ch = rem - hk * nchunk;
     const int r = order[rank];
-    const BlockRec bi = blk_ranked[rank];
-    const int I = r - bi.z;
+    const RowRec bi = rows_ranked[rank];
+    const int I = bi.I;
     const int tid = threadIdx.x, l = tid & 63, half = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, held in a scalar register
     const int hd = w >> 1, qh = w & 1;
@@ -168,8 +168,8 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         int row = 64 * qh + 32 * qt + (l & 31);
-        row = row < bi.y ? row : bi.y - 1;   // rows past a ragged end are masked in the reduction
-        const uint16_t *qp = Q + ((size_t)(bi.x + row) * hq + h) * kHeadDim + 8 * half;
+        row = row < bi.q_len ? row : bi.q_len - 1;   // rows past a ragged end are masked in the reduction
+        const uint16_t *qp = Q + ((size_t)(bi.q_tok0 + row) * hq + h) * kHeadDim + 8 * half;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qa[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
     }
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     const int ntile = I / 32 + 1;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(FP_LDS(char) *)smem;
     const uint32_t row_bytes = (uint32_t)hkv * kHeadDim * 2;
-    const char *pl_base = reinterpret_cast<const char *>(w < 2 ? kb_hi : kb_lo) + ((size_t)bi.z * hkv + hk) * kHeadDim * 2;
+    const char *pl_base = reinterpret_cast<const char *>(w < 2 ? kb_hi : kb_lo) + ((size_t)bi.kb_row0 * hkv + hk) * kHeadDim * 2;
     int ld_row[4];
     uint32_t ld_col[4];
 #pragma unroll
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
         if (active) {                                                                                     \
             f32x16 acc_[2];                                                                               \
             search_mma(smem, FP_BUF(jt_) + b_frag, qa, acc_);                                             \
-            const float2 v_ = search_reduce<RAGGED>(acc_, c, bi.y, 64 * qh, half);                        \
+            const float2 v_ = search_reduce<RAGGED>(acc_, c, bi.q_len, 64 * qh, half);                        \
             if (l < 32) {                                                                                 \
                 if (qh) {                                                                                 \
                     mbox[((jt_ & 1) * kSearchHeads + hd) * 32 + l] = v_;                                             \
@@ -246,7 +246,7 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
         __syncthreads();                                                                                  \
     } while (0)
 
-    if (bi.y < kBlock) {
+    if (bi.q_len < kBlock) {
         for (int jt = 0; jt < ntile; ++jt) FP_STEP(true, jt);
     } else {
         for (int jt = 0; jt < ntile; ++jt) FP_STEP(false, jt);
@@ -320,7 +320,7 @@ constexpr int kThresholdWaves = 4;   // rows per workgroup
 
 template <bool VEC>   // VEC: rows start on 16-byte boundaries (n_max % 4 == 0, aligned base)
 __global__ __launch_bounds__(256) void threshold_kernel(const float *__restrict__ scores,
-                                                        const BlockRec *__restrict__ blk, int m_total, int n_max,
+                                                        const RowRec *__restrict__ rows, int m_total, int n_max,
                                                         int n_pad, int hq, float alpha, int sinkB, int winB,
                                                         int32_t *__restrict__ idx, int32_t *__restrict__ cnt) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -330,7 +330,7 @@ __global__ __launch_bounds__(256) void threshold_kernel(const float *__restrict_
     if (wave >= hq * m_total) return;   // no barrier in this kernel: waves are independent
     float *buf = reinterpret_cast<float *>(smem) + (size_t)wv * n_pad;
     const int r = wave % m_total;   // wave = h*m_total + r
-    const int I = r - blk[r].z;
+    const int I = rows[r].I;
     const float *row = scores + (size_t)wave * n_max;
     int32_t *out = idx + (size_t)wave * n_max;
 

@@ -87,3 +87,24 @@ def test_plan_create_without_a_gpu_reports_device_error(lib):
 def test_largest_supported_sequence_is_accepted(lib):
     m, n, _ = B.fp_layout([0, 4096 * 128], 32, 4)
     assert (m, n) == (4096, 4096)
+
+
+def test_layout_with_a_kv_prefix(lib):
+    """Chunked prefill: rows count q-blocks, n_max counts key blocks; the prefix must be a block multiple."""
+    m, n, ro = B.fp_layout([0, 200, 328], 8, 2, cu_seqlens_k=[0, 200 + 384, 200 + 384 + 128 + 512])
+    assert (m, n) == (3, 5) and list(ro) == [0, 2, 3]
+    assert (m, n, list(ro)) == (lambda r: (r[0], r[1], list(r[2])))(oracle_layout([0, 200, 328], [0, 584, 1224]))
+    with pytest.raises(B.FlashPrefillError) as e:
+        B.fp_layout([0, 200], 8, 2, cu_seqlens_k=[0, 300])
+    assert e.value.status == B.FP_ERR_UNSUPPORTED
+    with pytest.raises(B.FlashPrefillError) as e:
+        B.fp_layout([0, 200], 8, 2, cu_seqlens_k=[0, 100])
+    assert e.value.status == B.FP_ERR_INVALID_ARG
+    with pytest.raises(B.FlashPrefillError) as e:
+        B.fp_layout([0, 128], 8, 2, cu_seqlens_k=[0, 4097 * 128])
+    assert e.value.status == B.FP_ERR_UNSUPPORTED
+
+
+def oracle_layout(cu, cuk):
+    import oracle
+    return oracle.layout(cu, cu_seqlens_k=cuk)
