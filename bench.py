@@ -185,6 +185,39 @@ def forced_density_run(w, host, density, steps, torch):
                 sparse_tflops=kept * PAIR_FLOPS / ms / 1e9)
 
 
+def alpha_sweep(w, host, steps, torch, factors=(0.5, 1.0, 2.0)):
+    """Threshold factor at 0.5x / 1x / 2x the workload's default: density, time of the threshold
+    and sparse-attention stages, and the output's distance from the own dense kernel's output."""
+    plan = host["plan"]
+    dQ, dK, dV, scores, idx, cnt, O = (host[k] for k in ("dQ", "dK", "dV", "scores", "idx", "cnt", "O"))
+    plan.fp_block_search(dQ, dK, scores)
+    Od = torch.empty_like(dQ)
+    plan.fp_dense_prefill(dQ, dK, dV, Od, want_lse=False)
+    pairs = causal_pairs(plan.row_offset, w.hq)
+    out = []
+    for f in factors:
+        a = w.alpha * f
+        plan.fp_threshold(scores, a, idx=idx, cnt=cnt)
+        plan.fp_sparse_prefill(dQ, dK, dV, idx, cnt, O, want_lse=False)
+        torch.cuda.synchronize()
+        e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        t_thr = t_att = 0.0
+        for _ in range(steps):
+            e[0].record(); plan.fp_threshold(scores, a, idx=idx, cnt=cnt)
+            e[1].record(); plan.fp_sparse_prefill(dQ, dK, dV, idx, cnt, O, want_lse=False)
+            e[2].record(); torch.cuda.synchronize()
+            t_thr += e[0].elapsed_time(e[1]); t_att += e[1].elapsed_time(e[2])
+        kept = int(cnt.sum().item())
+        mx, sm, n = 0.0, 0.0, 0
+        for lo in range(0, O.shape[0], 1 << 15):          # chunked so that the fp32 temporaries stay small
+            d = (O[lo:lo + (1 << 15)].float() - Od[lo:lo + (1 << 15)].float()).abs()
+            mx = max(mx, float(d.max().item())); sm += float(d.sum().item()); n += d.numel()
+        out.append(dict(alpha=a, density=kept / pairs, threshold_ms=t_thr / steps, sparse_attention_ms=t_att / steps,
+                        max_abs_vs_dense=mx, mean_abs_vs_dense=sm / n))
+    del Od
+    return out
+
+
 def cpu_baseline(w, host, res, torch, budget_pairs=16000):
     """Times the oracle (as it stands) on a bounded sample of the same workload's rows and scales
     by executed block pairs to one layer.  Also checks the GPU results on those rows."""
@@ -249,6 +282,9 @@ def main():
     ap.add_argument("--forced-density", type=float, nargs="*", default=[],
                     help="also time the sparse kernel alone on random causal lists of these densities")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--alpha-sweep", action="store_true",
+                    help="also run the threshold factor at 0.5x / 1x / 2x the default: density, stage times, distance "
+                         "of the sparse output from the own dense output")
     ap.add_argument("--sweep", action="store_true",
                     help="length sweep 4K..512K on the Qwen3-30B-A3B shape (block-coherent planting): per-stage ms, "
                          "speedup over the own dense kernel, and the sparse kernel alone at forced 60 %% / 6 %% density")
@@ -305,6 +341,10 @@ def main():
     for dens in a.forced_density:
         forced.append(forced_density_run(w, host, dens, a.steps, torch))
         log(f"[bench] forced density {json.dumps(forced[-1])}")
+    sweep_a = None
+    if a.alpha_sweep:
+        sweep_a = alpha_sweep(w, host, a.steps, torch)
+        log(f"[bench] alpha sweep {json.dumps(sweep_a)}")
     del host
     torch.cuda.empty_cache()
 
@@ -353,6 +393,7 @@ def main():
                            "frac": (res["dense_tflops"] or 0) / MFMA_BF16_PEAK_TFLOPS},
         "cpu_baseline": cpu,
         "forced_density": forced or None,
+        "alpha_sweep": sweep_a,
         "supplementary_block_coherent_planting": sup,
         "paper_context": "paper reports 27.78x at 256K and 1.71x at 4K vs FlashAttention 2.8.3 on NVIDIA H20 (real activations, density 3.5% at 256K)",
     }
