@@ -377,7 +377,7 @@ def main():
                                f"block 128, alpha={w.alpha}, sink 256, window 512, "
                                + ("generator as configured (N(0,1), RoPE 1e6, "
                                   f"{w.n_vert} single-token vertical plants, {w.n_slash} slash lags)" if w.mode == "literal"
-                                  else "block-coherent planting (supplementary recipe, see DESIGN.md)")},
+                                  else "block-coherent planting (supplementary recipe: planted directions shared by the tokens of a block)")},
         "stages_ms": res["ms"], "density": res["density"], "speedup_vs_own_dense": res["speedup_vs_own_dense"],
         "roofline": {"bound": "mfma", "kernel": "attn_kernel<sparse>", "achieved": res["sparse_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": res["sparse_tflops"] / MFMA_BF16_PEAK_TFLOPS,
