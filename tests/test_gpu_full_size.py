@@ -143,3 +143,46 @@ def test_llama_varlen_batch_and_alpha_sweep():
         if prev_cnt is not None:
             assert bool((cnt <= prev_cnt).all())            # lists nest as alpha grows
         prev_cnt = cnt.clone()
+
+
+def test_qwen3_shape_chunked_prefill_sampled_rows():
+    """The last 8K tokens of a 128K-token context as one prefill chunk (Qwen3 shape): sampled rows of
+    the chunk against the oracle's chunked form, and the lists' structural properties on every row."""
+    w = synth.config(2, "coherent")
+    print(f"\n[full size] {w.name}, chunk = last 8192 tokens", flush=True)
+    Q, K, V = synth.make_qkv(w, threads=16)
+    Tk, Tq = w.total_tokens, 8192
+    Qc = np.ascontiguousarray(Q[Tk - Tq:])
+    cuq, cuk = np.array([0, Tq], np.int32), np.array([0, Tk], np.int32)
+    plan = B.Plan(cuq, w.hq, w.hkv, cu_seqlens_k=cuk)
+    dQ, dK, dV = dev(Qc), dev(K), dev(V)
+    P = plan.fp_block_search(dQ, dK)
+    idx, cnt = plan.fp_threshold(P, w.alpha)
+    idx_f, cnt_f = plan.fp_search_select(dQ, dK, w.alpha)
+    O, lse = plan.fp_sparse_prefill(dQ, dK, dV, idx, cnt)
+    torch.cuda.synchronize()
+    m, n = plan.m_total, plan.n_max
+    pb = (Tk - Tq) // 128
+    assert (m, n) == (Tq // 128, Tk // 128)
+    # every row: causal, ascending, sink and window blocks present
+    I = torch.arange(m, device="cuda") + pb
+    valid = torch.arange(n, device="cuda")[None, None, :] < cnt[:, :, None]
+    assert bool(((idx >= 0) & (idx <= I[None, :, None]))[valid].all())
+    assert bool(((idx[:, :, 1:] > idx[:, :, :-1]) | ~valid[:, :, 1:]).all())
+    structural = ((idx < 2) | ((I[None, :, None] - idx) < 4)) & valid
+    assert bool((structural.sum(dim=2) == 6).all())
+    assert torch.equal(cnt_f, cnt) and bool((idx_f == idx)[valid].all())
+    rows = [0, 17, m - 1]
+    P_ref = oracle.block_search(Qc, K, cuq, rows=rows, cu_seqlens_k=cuk)
+    Pg = P.cpu().numpy()
+    for r in rows:
+        np.testing.assert_allclose(Pg[:, r, :r + pb + 1], P_ref[:, r, :r + pb + 1], rtol=5e-4, atol=1e-30)
+        assert not Pg[:, r, r + pb + 1:].any()
+    idx_h, cnt_h = idx.cpu().numpy(), cnt.cpu().numpy()
+    O_ref, lse_ref = oracle.sparse_prefill(Qc, K, V, cuq, idx_h, cnt_h, rows=rows, cu_seqlens_k=cuk)
+    toks = np.concatenate([np.arange(r * 128, (r + 1) * 128) for r in rows])
+    tt = torch.from_numpy(toks).cuda()
+    mx, mean = compare_O(O[tt].float().cpu().numpy(), O_ref[toks])
+    np.testing.assert_allclose(lse[:, tt].cpu().numpy(), lse_ref[:, toks], atol=LSE_ATOL, rtol=0)
+    print(f"chunked: density {cnt_h.sum() / (w.hq * sum(r + pb + 1 for r in range(m))):.3f}, sparse O max-abs {mx:.2e}")
+    plan.close()
