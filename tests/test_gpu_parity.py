@@ -23,6 +23,8 @@ CASES = [
     ("mha_g1", [700], 2, 2),
     ("g2", [900], 4, 2),
     ("g8_long_row", [5000], 8, 1),        # > 32 key blocks: more than one pooled-key tile per row
+    ("g3_odd_group", [1100, 300], 6, 2),  # odd group size: the search kernel's second head slot is idle in one chunk
+    ("many_short", [int(x) for x in np.random.default_rng(7).integers(1, 1500, size=40)], 4, 2),
 ]
 
 
@@ -158,3 +160,33 @@ def test_outputs_are_deterministic(case):
     Ob, _ = plan.fp_dense_prefill(case["dQ"], case["dK"], case["dV"])
     torch.cuda.synchronize()
     assert torch.equal(a, b) and torch.equal(Oa.view(torch.int16), Ob.view(torch.int16))
+
+
+def test_two_plans_on_two_streams():
+    """Plans own their workspaces, so two layers may run concurrently on two streams."""
+    ws = [synth.small("stream_a", [1400, 300], 8, 2, seed=21), synth.small("stream_b", [2100], 4, 4, seed=22)]
+    data = []
+    for w in ws:
+        Q, K, V = synth.make_qkv(w)
+        plan = B.Plan(w.cu_seqlens, w.hq, w.hkv)
+        data.append(dict(w=w, plan=plan, dQ=dev(Q), dK=dev(K), dV=dev(V)))
+    ref = []
+    for d in data:                                  # one after the other on the current stream
+        idx, cnt = d["plan"].fp_search_select(d["dQ"], d["dK"], 0.2)
+        O, lse = d["plan"].fp_sparse_prefill(d["dQ"], d["dK"], d["dV"], idx, cnt)
+        ref.append((cnt.clone(), O.clone(), lse.clone()))
+    torch.cuda.synchronize()
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    out = [None, None]
+    for rep in range(3):
+        for i, d in enumerate(data):
+            with torch.cuda.stream(streams[i]):
+                idx, cnt = d["plan"].fp_search_select(d["dQ"], d["dK"], 0.2, stream=streams[i])
+                O, lse = d["plan"].fp_sparse_prefill(d["dQ"], d["dK"], d["dV"], idx, cnt, stream=streams[i])
+                out[i] = (cnt, O, lse)
+        torch.cuda.synchronize()
+        for got, want in zip(out, ref):
+            for a, b in zip(got, want):
+                assert torch.equal(a, b)
+    for d in data:
+        d["plan"].close()
