@@ -186,15 +186,18 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
     ok = ok && hipMemcpy(p->d_kblk, kblk.data(), kblk.size() * sizeof(fp::KeyBlockRec), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_order, order.data(), order.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_rows_ranked, rows_ranked.data(), rows.size() * sizeof(fp::RowRec), hipMemcpyHostToDevice) == hipSuccess;
+    // The dynamic-LDS ceilings are per kernel, not per plan: they are set to what the largest
+    // supported shape needs, so that plans of different sizes can be alive together.
+    const int search_lds_max = fp::kSearchStageBytes + fp::kSearchRowHeader + fp::kSearchHeads * kMaxBlocksPerSeq * (int)sizeof(float);
+    const int thr_lds_max = fp::kThresholdWaves * kMaxBlocksPerSeq * (int)sizeof(float);
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, search_lds_max) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)p->search_lds) == hipSuccess;
-    const int thr_lds = (int)(fp::kThresholdWaves * ((L.n_max + 63) / 64 * 64) * sizeof(float));
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, search_lds_max) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, thr_lds) == hipSuccess;
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, thr_lds_max) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, thr_lds) == hipSuccess;
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, thr_lds_max) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<false>),

@@ -126,3 +126,38 @@ def test_chunk_equals_the_tail_of_a_plain_prefill_bitwise(case):
     st = torch.from_numpy(sel).cuda()
     assert torch.equal(Of[st], Oc) and torch.equal(lf[:, st], lc)
     full.close()
+
+
+def test_largest_row_next_to_a_small_plan():
+    """One query block against 4096 key blocks (the most a sequence may have), with a small plan
+    created afterwards: kernel limits are per library, not per plan, so the large plan still runs."""
+    rng = np.random.default_rng(3)
+    Tk, hq, hkv = 4096 * 128, 2, 1
+    u = rng.standard_normal(128).astype(np.float32); u /= np.linalg.norm(u)
+    Kf = rng.standard_normal((Tk, hkv, 128)).astype(np.float32)
+    for j in rng.choice(4096, size=12, replace=False):      # a dozen key blocks that stand out
+        Kf[j * 128:(j + 1) * 128] += 4.0 * u
+    K = synth.f32_to_bf16_bits(Kf)
+    V = synth.f32_to_bf16_bits(rng.standard_normal((Tk, hkv, 128)).astype(np.float32))
+    Q = synth.f32_to_bf16_bits(rng.standard_normal((128, hq, 128)).astype(np.float32) + 6.0 * u)
+    cuq, cuk = [0, 128], [0, Tk]
+    big = B.Plan(cuq, hq, hkv, cu_seqlens_k=cuk)
+    small = B.Plan([0, 256], hq, hkv)
+    assert (big.m_total, big.n_max) == (1, 4096)
+    dQ, dK, dV = dev(Q), dev(K), dev(V)
+    P = big.fp_block_search(dQ, dK)
+    idx, cnt = big.fp_threshold(P, 0.5)
+    idx_f, cnt_f = big.fp_search_select(dQ, dK, 0.5)
+    torch.cuda.synchronize()
+    P_ref = oracle.block_search(Q, K, cuq, cu_seqlens_k=cuk)
+    np.testing.assert_allclose(P.cpu().numpy(), P_ref, rtol=5e-4, atol=1e-30)
+    idx_r, cnt_r = oracle.threshold(P.cpu().numpy(), cuq, 0.5, cu_seqlens_k=cuk)
+    compare_lists_exact(idx.cpu().numpy(), cnt.cpu().numpy(), idx_r, cnt_r)
+    compare_lists_exact(idx_f.cpu().numpy(), cnt_f.cpu().numpy(), idx_r, cnt_r)
+    O, lse = big.fp_sparse_prefill(dQ, dK, dV, idx, cnt)
+    torch.cuda.synchronize()
+    O_ref, lse_ref = oracle.sparse_prefill(Q, K, V, cuq, idx_r, cnt_r, cu_seqlens_k=cuk)
+    compare_O(O, O_ref)
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, atol=LSE_ATOL, rtol=0)
+    print(f"4096-block row: kept {int(cnt_r.sum())} of {hq * 4096} pairs")
+    big.close(); small.close()
