@@ -99,6 +99,7 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0):
     search_ms, thr_ms, sparse_ms = st.mean(axis=0)
     kept = int(cnt.sum().item())
     pairs = causal_pairs(plan.row_offset, hq)
+    per_head = (cnt.sum(dim=1).double() / (pairs / hq)).cpu().numpy()
 
     dense_ms = None
     if dense_runs > 0:
@@ -140,11 +141,15 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0):
         ms=dict(search=float(search_ms), threshold=float(thr_ms), sparse_attention=float(sparse_ms),
                 end_to_end=float(search_ms + thr_ms + sparse_ms), end_to_end_wall=float(wall_ms),
                 search_select_fused=float(fused_ms), end_to_end_fused=float(fused_ms + sparse_ms), dense=dense_ms),
-        density=kept / pairs, kept_pairs=kept, causal_pairs=pairs,
+        ms_median=dict(zip(("search", "threshold", "sparse_attention"), map(float, np.median(st, axis=0)))),
+        ms_min=dict(zip(("search", "threshold", "sparse_attention"), map(float, st.min(axis=0)))),
+        density=kept / pairs, density_per_head_min=float(per_head.min()), density_per_head_max=float(per_head.max()),
+        kept_pairs=kept, causal_pairs=pairs,
         speedup_vs_own_dense=(dense_ms / float(search_ms + thr_ms + sparse_ms)) if dense_ms else None,
         speedup_vs_own_dense_fused=(dense_ms / float(fused_ms + sparse_ms)) if dense_ms else None,
         search_gbs=search_bytes / search_ms / 1e6,
         search_mfma_tflops=pairs * 2 * 128 * 128 * 2 / search_ms / 1e9,   # two bf16 passes (hi, lo) per pair
+        search_exp2_per_s=pairs * 128 / (search_ms * 1e-3),                # one exponential per (query, pooled key)
         threshold_gbs=thr_bytes / thr_ms / 1e6,
         sparse_tflops=kept * PAIR_FLOPS / sparse_ms / 1e9,
         dense_tflops=(pairs * PAIR_FLOPS / dense_ms / 1e9) if dense_ms else None,
@@ -378,7 +383,9 @@ def main():
                                + ("generator as configured (N(0,1), RoPE 1e6, "
                                   f"{w.n_vert} single-token vertical plants, {w.n_slash} slash lags)" if w.mode == "literal"
                                   else "block-coherent planting (supplementary recipe: planted directions shared by the tokens of a block)")},
-        "stages_ms": res["ms"], "density": res["density"], "speedup_vs_own_dense": res["speedup_vs_own_dense"],
+        "stages_ms": res["ms"], "stages_ms_median": res["ms_median"], "stages_ms_min": res["ms_min"],
+        "density": res["density"], "density_per_head": [res["density_per_head_min"], res["density_per_head_max"]],
+        "speedup_vs_own_dense": res["speedup_vs_own_dense"], "speedup_vs_own_dense_fused": res["speedup_vs_own_dense_fused"],
         "roofline": {"bound": "mfma", "kernel": "attn_kernel<sparse>", "achieved": res["sparse_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": res["sparse_tflops"] / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, "fp::attn_kernel<true>") or {}).get("bytes"),
@@ -387,6 +394,7 @@ def main():
                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["search_gbs"] / HBM_PEAK_GBS,
                             "mfma_tflops_two_pass": res["search_mfma_tflops"],
                             "mfma_frac_two_pass": res["search_mfma_tflops"] / MFMA_BF16_PEAK_TFLOPS,
+                            "exp2_per_s": res["search_exp2_per_s"],
                             "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, "fp::search_kernel<false>") or {}).get("bytes")},
         "roofline_dense": {"bound": "mfma", "kernel": "attn_kernel<dense>", "achieved": res["dense_tflops"],
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
