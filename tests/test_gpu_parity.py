@@ -190,3 +190,27 @@ def test_two_plans_on_two_streams():
                 assert torch.equal(a, b)
     for d in data:
         d["plan"].close()
+
+
+def test_custom_softmax_scale_and_eps():
+    """A softmax scale other than 1/sqrt(d) and an eps large enough to matter, against the oracle."""
+    w = synth.small("custom_scale", [1700, 260], 8, 2, seed=31)
+    Q, K, V = synth.make_qkv(w)
+    cu, tau, eps = w.cu_seqlens, 0.05, 5.0
+    plan = B.Plan(cu, w.hq, w.hkv, scale=tau)
+    dQ, dK, dV = dev(Q), dev(K), dev(V)
+    P_ref = oracle.block_search(Q, K, cu, tau=tau, eps=eps)
+    P = plan.fp_block_search(dQ, dK, eps=eps)
+    torch.cuda.synchronize()
+    compare_scores(P.cpu().numpy(), P_ref, cu)
+    assert abs(float(P_ref[0, 5].sum()) - 1.0) > 1e-2          # eps is visible in the normalisation
+    idx_r, cnt_r = oracle.threshold(P_ref, cu, 0.3)
+    idx_f, cnt_f = plan.fp_search_select(dQ, dK, 0.3, eps=eps)
+    torch.cuda.synchronize()
+    compare_lists_banded(idx_f.cpu().numpy(), cnt_f.cpu().numpy(), P_ref, cu, 0.3)
+    O_ref, lse_ref = oracle.sparse_prefill(Q, K, V, cu, idx_r, cnt_r, tau=tau)
+    O, lse = plan.fp_sparse_prefill(dQ, dK, dV, torch.from_numpy(idx_r).cuda(), torch.from_numpy(cnt_r).cuda())
+    torch.cuda.synchronize()
+    compare_O(O, O_ref)
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, atol=LSE_ATOL, rtol=0)
+    plan.close()
