@@ -36,10 +36,10 @@ __device__ __forceinline__ s16x4 lds_read_tr(const char *p) {
  * Per tile and wave:
  *   S^T = K Q^T  (keys x queries, 16 MFMA 32x32x16): the query index is the lane column, so the
  *         row max and row sum of the softmax are reductions over a lane's own registers plus one
- *         exchange with lane^32;
+ *         exchange between the wave's halves;
  *   causal mask only if the tile belongs to the diagonal block (Alg. 3, is_diag);
- *   online softmax in base 2: p = 2^(c*s - c*m), the accumulator is rescaled only when some
- *         row's max moved;
+ *   online softmax in base 2: p = 2^(c*s - c*m) with m a reference point that follows the row
+ *         max lazily (see attn_new_max), so the accumulator is rescaled a few times per row;
  *   O^T += V^T P^T (16 MFMA): P^T is already in B-operand layout (registers of S^T, packed to
  *         bf16), V^T fragments come from the row-major V tile through LDS transpose reads.
  *
