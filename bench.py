@@ -45,22 +45,34 @@ def profiled_traffic(workload_tag, kernel):
     return None
 
 
-def causal_pairs(row_offset, hq):
+def causal_pairs(row_offset, hq, cu=None, cuk=None):
+    """Causal (q-block, k-block) pairs over all heads; with key-side lengths, q-block I of a chunk
+    that follows a prefix of PB blocks has I + PB + 1 of them."""
     n = np.diff(row_offset).astype(np.int64)
-    return int((n * (n + 1) // 2).sum()) * hq
+    pb = 0 if cuk is None else (np.diff(np.asarray(cuk, np.int64)) - np.diff(np.asarray(cu, np.int64))) // 128
+    return int((n * (n + 1) // 2 + n * pb).sum()) * hq
 
 
-def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0):
+def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk=0):
     """Times the path on one workload; returns a dict of measurements (times in ms).  With
     min_timed_ms > 0 (the length sweep) short workloads take more warm-up and timed steps, so that
-    the timed region lasts at least that long and the clocks have settled."""
+    the timed region lasts at least that long and the clocks have settled.  chunk > 0: chunked
+    prefill, the queries are the last `chunk` tokens of every sequence (all of a shorter one)."""
     from paper_2603_06199_amd import synth
     t0 = time.time()
     Q, K, V = synth.make_qkv(w, threads=min(16, os.cpu_count() or 8))
     log(f"[bench] {w.name}: generated {Q.nbytes / 2**30:.2f} GiB Q in {time.time() - t0:.1f}s")
     cu = w.cu_seqlens
+    cuk = None
+    if chunk > 0:
+        if chunk % 128:
+            raise SystemExit("--chunk must be a multiple of the block size (128)")
+        cuk = np.asarray(cu, np.int64)
+        qlen = np.minimum(np.diff(cuk), chunk)
+        Q = np.ascontiguousarray(np.concatenate([Q[cuk[i + 1] - qlen[i]:cuk[i + 1]] for i in range(len(qlen))]))
+        cu = np.concatenate([[0], np.cumsum(qlen)]).astype(np.int32)
     dQ, dK, dV = B.to_device_bf16(Q), B.to_device_bf16(K), B.to_device_bf16(V)
-    plan = B.Plan(cu, w.hq, w.hkv)
+    plan = B.Plan(cu, w.hq, w.hkv, cu_seqlens_k=cuk)
     hq, m, n = w.hq, plan.m_total, plan.n_max
     scores = torch.empty((hq, m, n), dtype=torch.float32, device="cuda")
     idx = torch.empty((hq, m, n), dtype=torch.int32, device="cuda")
@@ -98,7 +110,7 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0):
     st = np.array([[e[j].elapsed_time(e[j + 1]) for j in range(3)] for e in evs])
     search_ms, thr_ms, sparse_ms = st.mean(axis=0)
     kept = int(cnt.sum().item())
-    pairs = causal_pairs(plan.row_offset, hq)
+    pairs = causal_pairs(plan.row_offset, hq, cu, cuk)
     per_head = (cnt.sum(dim=1).double() / (pairs / hq)).cpu().numpy()
 
     dense_ms = None
@@ -134,10 +146,10 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0):
     assert int(cnt.sum().item()) == kept
 
     T = plan.T
-    search_bytes = 2 * T * 128 * (w.hq + w.hkv) + 4 * pairs          # Q once + K once + one fp32 per causal pair
+    search_bytes = 2 * 128 * (T * w.hq + plan.Tk * w.hkv) + 4 * pairs   # Q once + K once + one fp32 per causal pair
     thr_bytes = 4 * pairs + 4 * kept + 4 * hq * m
     res = dict(
-        workload=w.name, tokens=T, hq=w.hq, hkv=w.hkv, alpha=w.alpha, planting=w.mode, timed_steps=steps,
+        workload=w.name, tokens=T, key_tokens=plan.Tk, hq=w.hq, hkv=w.hkv, alpha=w.alpha, planting=w.mode, timed_steps=steps,
         ms=dict(search=float(search_ms), threshold=float(thr_ms), sparse_attention=float(sparse_ms),
                 end_to_end=float(search_ms + thr_ms + sparse_ms), end_to_end_wall=float(wall_ms),
                 search_select_fused=float(fused_ms), end_to_end_fused=float(fused_ms + sparse_ms), dense=dense_ms),
@@ -287,6 +299,9 @@ def main():
     ap.add_argument("--forced-density", type=float, nargs="*", default=[],
                     help="also time the sparse kernel alone on random causal lists of these densities")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--chunk", type=int, default=0,
+                    help="chunked prefill: time the path for the last CHUNK tokens of every sequence as queries against "
+                         "the whole sequence's keys (multiple of 128); prints its own JSON line")
     ap.add_argument("--alpha-sweep", action="store_true",
                     help="also run the threshold factor at 0.5x / 1x / 2x the default: density, stage times, distance "
                          "of the sparse output from the own dense output")
@@ -329,6 +344,20 @@ def main():
                           "paper_context": "paper (NVIDIA H20, real activations): speedup vs FlashAttention 1.71/2.79/4.48/6.94/11.45/18.67/27.78x "
                                            "at 4K..256K; densities 70.4/46.0/29.0/17.6/10.0/5.8/3.5 %",
                           "sweep": rows}), flush=True)
+        return
+
+    if a.chunk > 0:
+        w = synth.config(a.config, a.planting)
+        r, h = run_workload(w, a.steps, a.warmup, dense_runs=2, torch=torch, B=B, min_timed_ms=100.0, chunk=a.chunk)
+        del h
+        print(json.dumps({"metric": "chunked sparse prefill ms/layer (block search + threshold + block-sparse attention)",
+                          "value": r["ms"]["end_to_end"], "unit": "ms/layer", "n_gpus": 1, "steps": r["timed_steps"],
+                          "warmup": a.warmup, "ms_per_step": r["ms"]["end_to_end"], "higher_is_better": False,
+                          "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                          "config": {"workload": f"{w.name}: last {a.chunk} tokens of each sequence as one prefill chunk, "
+                                                 f"Hq={w.hq} Hkv={w.hkv} d=128, {r['tokens']} query / {r['key_tokens']} key tokens"},
+                          "stages_ms": r["ms"], "density": r["density"], "speedup_vs_own_dense": r["speedup_vs_own_dense"],
+                          "sparse_tflops": r["sparse_tflops"], "dense_tflops": r["dense_tflops"]}), flush=True)
         return
 
     w = synth.config(a.config, a.planting)
