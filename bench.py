@@ -235,6 +235,24 @@ def alpha_sweep(w, host, steps, torch, factors=(0.5, 1.0, 2.0)):
     return out
 
 
+def library_gemm_tflops(torch, n=8192):
+    """A plain library bf16 GEMM (n^3, torch.matmul) on the same box: what a dense contraction with
+    no softmax in it reaches at the clocks the chip sustains.  Context for the MFMA fractions."""
+    a = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+    for _ in range(3):
+        c = a @ b
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(50):
+        c = a @ b
+    e1.record()
+    torch.cuda.synchronize()
+    del c
+    return 2 * n ** 3 / (e0.elapsed_time(e1) / 50) / 1e9
+
+
 def cpu_baseline(w, host, res, torch, budget_pairs=16000):
     """Times the oracle (as it stands) on a bounded sample of the same workload's rows and scales
     by executed block pairs to one layer.  Also checks the GPU results on those rows."""
@@ -299,6 +317,8 @@ def main():
     ap.add_argument("--forced-density", type=float, nargs="*", default=[],
                     help="also time the sparse kernel alone on random causal lists of these densities")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gemm-reference", action="store_true",
+                    help="also time a library bf16 GEMM (8192^3) as context for the MFMA fractions")
     ap.add_argument("--chunk", type=int, default=0,
                     help="chunked prefill: time the path for the last CHUNK tokens of every sequence as queries against "
                          "the whole sequence's keys (multiple of 128); prints its own JSON line")
@@ -431,6 +451,7 @@ def main():
         "cpu_baseline": cpu,
         "forced_density": forced or None,
         "alpha_sweep": sweep_a,
+        "library_gemm_bf16_tflops": library_gemm_tflops(torch) if a.gemm_reference else None,
         "supplementary_block_coherent_planting": sup,
         "paper_context": "paper reports 27.78x at 256K and 1.71x at 4K vs FlashAttention 2.8.3 on NVIDIA H20 (real activations, density 3.5% at 256K)",
     }
