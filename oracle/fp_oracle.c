@@ -257,6 +257,11 @@ int fpo_threshold(const float *scores, int nseq, const int32_t *cu, const int32_
 /* softmax(tau q.k) V over an explicit key set, two passes, fp64. */
 static void attend_row(const uint16_t *q, const uint16_t *K, const uint16_t *V, int hkv, int hk, int d, double tau,
                        const int *keys, int nkeys, double *logit, float *o, float *lse) {
+    if (nkeys == 0) { /* not a paper case: a query with no visible key (empty list) gets O = 0, lse = -inf */
+        for (int c = 0; c < d; ++c) o[c] = 0.0f;
+        if (lse) *lse = -INFINITY;
+        return;
+    }
     double mx = -INFINITY;
     double qd[d];
     for (int c = 0; c < d; ++c) qd[c] = bf16_val(q[c]);

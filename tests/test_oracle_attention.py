@@ -164,3 +164,19 @@ def test_row_subset_equals_full():
         np.testing.assert_array_equal(Op[r * 128:(r + 1) * 128], O[r * 128:(r + 1) * 128])
         np.testing.assert_array_equal(lp[:, r * 128:(r + 1) * 128], l[:, r * 128:(r + 1) * 128])
     assert np.all(Op[:128] == 0) and np.all(Op[256:512] == 0)
+
+
+def test_empty_list_gives_zero_output_and_minus_infinite_lse():
+    """Not a paper case: a query whose list holds no visible key.  The reading taken is O = 0 and
+    lse = -inf (the log of an empty sum); every other row is unaffected."""
+    Q, K, V = synth.random_qkv([300], 2, 1, 128, seed=5)
+    cu = [0, 300]
+    idx, cnt = oracle.threshold(oracle.block_search(Q, K, cu), cu, 0.0)
+    O_all, lse_all = oracle.sparse_prefill(Q, K, V, cu, idx, cnt)
+    cnt2 = cnt.copy()
+    cnt2[:, 1] = 0
+    O, lse = oracle.sparse_prefill(Q, K, V, cu, idx, cnt2)
+    assert not O[128:256].any() and np.all(np.isneginf(lse[:, 128:256]))
+    keep = np.r_[0:128, 256:300]
+    np.testing.assert_array_equal(O[keep], O_all[keep])
+    np.testing.assert_array_equal(lse[:, keep], lse_all[:, keep])
