@@ -12,9 +12,12 @@ from paper_2603_06199_amd import synth
 # for scores that flush to zero (the GPU's exp2 has no denormal results).
 O_MAX_ABS, O_MEAN_ABS = 2e-2, 2e-3
 SCORE_RTOL, SCORE_ATOL = 5e-4, 1e-30
-# lse: the kernel sums the bf16-rounded probabilities (the values that multiply V), each within
-# 2^-9 relative of the exact one, so log2 of the row sum is within log2(1 + 2^-9) = 2.8e-3.
-LSE_ATOL = 4e-3
+# lse: the kernel sums the bf16-rounded probabilities (the values that multiply V).  bf16 keeps 8
+# significant bits, so round-to-nearest is off by at most 2^-8 relative (at the low end of a
+# binade; 2^-9 at the high end): if every term of a row leans the same way, log2 of the row sum
+# is off by log2(1 + 2^-8) = 5.6e-3.  Typical rows are far inside that; a randomised sweep met
+# 4.1e-3 once in 8343 queries.
+LSE_ATOL = 6e-3
 BAND = 1e-3           # near-threshold band: |score - alpha*max| <= BAND * alpha*max
 
 
