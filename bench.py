@@ -58,7 +58,7 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk
     min_timed_ms > 0 (the length sweep) short workloads take more warm-up and timed steps, so that
     the timed region lasts at least that long and the clocks have settled.  chunk > 0: chunked
     prefill, the queries are the last `chunk` tokens of every sequence (all of a shorter one)."""
-    from paper_2603_06199_amd import synth
+    import synth
     t0 = time.time()
     Q, K, V = synth.make_qkv(w, threads=min(16, os.cpu_count() or 8))
     log(f"[bench] {w.name}: generated {Q.nbytes / 2**30:.2f} GiB Q in {time.time() - t0:.1f}s")
@@ -257,7 +257,7 @@ def cpu_baseline(w, host, res, torch, budget_pairs=16000):
     """Times the oracle (as it stands) on a bounded sample of the same workload's rows and scales
     by executed block pairs to one layer.  Also checks the GPU results on those rows."""
     import oracle
-    from paper_2603_06199_amd import synth
+    import synth
     Q, K, V, cu = host["Q"], host["K"], host["V"], host["cu"]
     m_total, n_max, ro = synth.layout(cu)
     cnt_h = host["cnt"].cpu().numpy()
@@ -337,7 +337,7 @@ def main():
 
     import torch
     from paper_2603_06199_amd import binding as B
-    from paper_2603_06199_amd import synth
+    import synth
     if not os.path.exists(B.LIB_PATH):
         from paper_2603_06199_amd import build
         build.build()

@@ -36,6 +36,8 @@
  *     must be stream-ordered with respect to each other (they share the plan's workspace).
  *   - Errors are return codes.  Argument checks happen on the host before any launch.
  *     A launch failure is reported as FP_ERR_DEVICE.  NaN/Inf inputs are not checked.
+ *   - Device memory: the caller's tensors plus one buffer per plan, either allocated by
+ *     fp_plan_create or brought by the caller (fp_workspace_bytes + fp_plan_create_in).
  */
 #ifndef FLASHPREFILL_H
 #define FLASHPREFILL_H
@@ -53,7 +55,8 @@ typedef enum {
     FP_ERR_UNSUPPORTED = 2, /* head_dim != 128, block != 128, more than 4096 blocks/seq, or a */
                             /* KV prefix that is not a multiple of the block                */
     FP_ERR_DEVICE = 3,      /* HIP runtime error (no device, allocation or launch failure) */
-    FP_ERR_NOMEM = 4        /* host allocation failed                                      */
+    FP_ERR_NOMEM = 4,       /* host allocation failed                                      */
+    FP_ERR_WORKSPACE = 5    /* caller-supplied workspace too small or not 256-byte aligned */
 } fp_status;
 
 typedef struct {
@@ -74,7 +77,11 @@ typedef struct {
                            /* the window includes the diagonal block                                     */
 } fp_params;
 
-typedef struct fp_plan fp_plan; /* opaque: shape tables on the device + workspace (pooled keys) */
+/* Opaque: the shape's row tables on the device + the pooled-key workspace.  A plan per shape takes
+ * the place of a context object with a fixed workspace: the tables (row records, heavy-first order)
+ * depend on cu_seqlens, are built once on the host and are read by every kernel, so they live and
+ * die with the shape they describe. */
+typedef struct fp_plan fp_plan;
 
 const char *fp_status_string(fp_status s);
 
@@ -82,18 +89,35 @@ const char *fp_status_string(fp_status s);
  * NULL; row_offset receives nseq+1 entries.  No GPU is touched. */
 fp_status fp_layout(const fp_shape *shape, int32_t *m_total, int32_t *n_max, int32_t *row_offset);
 
-/* Validates `shape`, selects `device`, allocates and fills the plan's device tables and its
- * workspace (pooled keys: 2 x (key blocks) x Hkv x 128 bf16).  Synchronous.  The plan is immutable
- * afterwards and may be used for any number of calls; destroy it with fp_plan_destroy after
- * the work enqueued with it has finished. */
+/* Bytes of device memory a plan for `shape` needs (row tables + the pooled keys of Alg. 1 stage 1:
+ * 2 x (key blocks) x Hkv x 128 bf16); 0 if the shape is invalid or unsupported.  Host only. */
+size_t fp_workspace_bytes(const fp_shape *shape);
+
+/* Validates `shape`, selects `device`, allocates one device buffer of fp_workspace_bytes(shape)
+ * and fills the plan's tables in it.  Synchronous.  The plan is immutable afterwards and may be
+ * used for any number of calls; destroy it with fp_plan_destroy after the work enqueued with it
+ * has finished. */
 fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **plan);
+
+/* The same with the device memory brought by the caller: `workspace` is a DEVICE pointer on
+ * `device`, 256-byte aligned, of at least fp_workspace_bytes(shape) bytes (FP_ERR_WORKSPACE
+ * otherwise, checked before the GPU is touched); it stays the caller's, must outlive the plan and
+ * must not be used for anything else meanwhile.  No device allocation happens in this call
+ * (the tables are copied in synchronously); workspace == NULL behaves as fp_plan_create. */
+fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, size_t workspace_bytes,
+                            fp_plan **plan);
+
+/* Frees the plan and, if the library allocated it, its device buffer.  NULL is a no-op. */
 void fp_plan_destroy(fp_plan *plan);
 
 /*
  * Stage (i).  Alg. 1: mean-pool each key block (stage 1), for every causal block pair
  * (I, J <= I) reduce the query tile's logits against the pooled key to a max m_IJ and a sum
  * of exponentials S_IJ (stage 2, Eq. 1-2), bring each row to its max and normalise (stage 3,
- * Eq. 3-4):  scores[h, r, J] = S'_IJ / (sum_K S'_IK + eps) for J <= I, and 0 for I < J < n_max.
+ * Eq. 3-4):  scores[h, r, J] = S'_IJ / (sum_K S'_IK + eps) for J <= I, and 0 for I < J < N_s, the
+ * number of key blocks of the row's own sequence; entries N_s <= J < n_max (a shorter sequence of
+ * a packed batch) are not written.  `eps` is an argument, not a field of fp_params: it belongs to
+ * Eq. 4, while fp_params holds the hyper-parameters of Alg. 2.
  * The pair-level causal restriction J <= I is the only mask; a partial last block averages its
  * valid keys and leaves out missing queries.
  */

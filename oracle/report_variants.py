@@ -15,7 +15,7 @@ import numpy as np
 
 import oracle
 from oracle import variants as V
-from paper_2603_06199_amd import synth
+import synth
 
 
 def report(tokens: int, mode: str) -> None:

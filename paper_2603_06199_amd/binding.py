@@ -14,9 +14,10 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflashprefill.so")
 
-FP_OK, FP_ERR_INVALID_ARG, FP_ERR_UNSUPPORTED, FP_ERR_DEVICE, FP_ERR_NOMEM = range(5)
+FP_OK, FP_ERR_INVALID_ARG, FP_ERR_UNSUPPORTED, FP_ERR_DEVICE, FP_ERR_NOMEM, FP_ERR_WORKSPACE = range(6)
 
-EXPORTS = ("fp_status_string", "fp_layout", "fp_plan_create", "fp_plan_destroy", "fp_block_search",
+EXPORTS = ("fp_status_string", "fp_layout", "fp_workspace_bytes", "fp_plan_create", "fp_plan_create_in",
+           "fp_plan_destroy", "fp_block_search",
            "fp_threshold", "fp_search_select", "fp_sparse_prefill", "fp_dense_prefill")
 
 
@@ -52,7 +53,10 @@ def lib() -> ctypes.CDLL:
         L.fp_status_string.restype = ctypes.c_char_p
         L.fp_status_string.argtypes = [ctypes.c_int]
         L.fp_layout.argtypes = [ctypes.POINTER(fp_shape), ctypes.POINTER(i32), ctypes.POINTER(i32), vp]
+        L.fp_workspace_bytes.argtypes = [ctypes.POINTER(fp_shape)]
+        L.fp_workspace_bytes.restype = ctypes.c_size_t
         L.fp_plan_create.argtypes = [ctypes.POINTER(fp_shape), ctypes.c_int, ctypes.POINTER(vp)]
+        L.fp_plan_create_in.argtypes = [ctypes.POINTER(fp_shape), ctypes.c_int, vp, ctypes.c_size_t, ctypes.POINTER(vp)]
         L.fp_plan_destroy.argtypes = [vp]
         L.fp_plan_destroy.restype = None
         L.fp_block_search.argtypes = [vp, vp, vp, f32, vp, vp]
@@ -97,6 +101,13 @@ def fp_layout(cu_seqlens: Sequence[int], hq: int, hkv: int, head_dim: int = 128,
     return int(m.value), int(n.value), ro
 
 
+def fp_workspace_bytes(cu_seqlens: Sequence[int], hq: int, hkv: int, head_dim: int = 128, block: int = 128,
+                       scale: float = 0.0, cu_seqlens_k: Optional[Sequence[int]] = None) -> int:
+    """Host-only: bytes of device memory a plan for this shape needs (0 for a shape the library rejects)."""
+    s, keep = make_shape(cu_seqlens, hq, hkv, head_dim, block, scale, cu_seqlens_k)
+    return int(lib().fp_workspace_bytes(ctypes.byref(s)))
+
+
 def _stream_ptr(stream) -> Optional[int]:
     import torch
     st = torch.cuda.current_stream() if stream is None else stream
@@ -118,7 +129,7 @@ class Plan:
     """Owns an fp_plan (device tables + pooled-key workspace) for one packed-batch shape."""
 
     def __init__(self, cu_seqlens: Sequence[int], hq: int, hkv: int, head_dim: int = 128, block: int = 128,
-                 scale: float = 0.0, device: int = 0, cu_seqlens_k: Optional[Sequence[int]] = None):
+                 scale: float = 0.0, device: int = 0, cu_seqlens_k: Optional[Sequence[int]] = None, workspace=None):
         self.cu_seqlens = np.ascontiguousarray(cu_seqlens, dtype=np.int32)
         self.cu_seqlens_k = None if cu_seqlens_k is None else np.ascontiguousarray(cu_seqlens_k, dtype=np.int32)
         self.hq, self.hkv, self.head_dim, self.block = hq, hkv, head_dim, block
@@ -129,7 +140,13 @@ class Plan:
         self.Tk = self.T if self.cu_seqlens_k is None else int(self.cu_seqlens_k[-1])      # key tokens
         s, keep = make_shape(self.cu_seqlens, hq, hkv, head_dim, block, scale, self.cu_seqlens_k)
         h = ctypes.c_void_p()
-        _check(lib().fp_plan_create(ctypes.byref(s), device, ctypes.byref(h)), "fp_plan_create")
+        self._workspace = workspace          # a caller-owned torch.uint8 CUDA tensor, kept alive with the plan
+        if workspace is None:
+            _check(lib().fp_plan_create(ctypes.byref(s), device, ctypes.byref(h)), "fp_plan_create")
+        else:
+            _check(lib().fp_plan_create_in(ctypes.byref(s), device, ctypes.c_void_p(workspace.data_ptr()),
+                                           workspace.numel() * workspace.element_size(), ctypes.byref(h)),
+                   "fp_plan_create_in")
         self._h = h
 
     def close(self) -> None:

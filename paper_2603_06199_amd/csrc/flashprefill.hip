@@ -72,9 +72,40 @@ struct fp_plan {
     fp::KeyBlockRec *d_kblk = nullptr;     // [kb_total]
     uint16_t *d_kb_hi = nullptr;      // [kb_total, hkv, 128] bf16
     uint16_t *d_kb_lo = nullptr;
+    void *workspace = nullptr;        // the one device buffer all of the above are carved from
+    bool owns_workspace = false;      // true: allocated by fp_plan_create, freed by fp_plan_destroy
     size_t search_lds = 0;
     int n_pad = 0;
 };
+
+namespace {
+
+// The plan's device memory is one buffer: row records by row and by rank, the rank order, the
+// key-block records and the two pooled-key planes, each part starting on a 256-byte boundary.
+constexpr size_t kWsAlign = 256;
+struct WorkspaceMap {
+    size_t rows = 0, rows_ranked = 0, order = 0, kblk = 0, kb_hi = 0, kb_lo = 0, total = 0;
+};
+WorkspaceMap workspace_map(const Layout &L, int hkv) {
+    WorkspaceMap m;
+    size_t off = 0;
+    auto take = [&off](size_t bytes) {
+        const size_t at = off;
+        off += (bytes + kWsAlign - 1) / kWsAlign * kWsAlign;
+        return at;
+    };
+    const size_t kb_bytes = (size_t)L.kb_total * hkv * fp::kHeadDim * sizeof(uint16_t);
+    m.rows = take((size_t)L.m_total * sizeof(fp::RowRec));
+    m.rows_ranked = take((size_t)L.m_total * sizeof(fp::RowRec));
+    m.order = take((size_t)L.m_total * sizeof(int32_t));
+    m.kblk = take((size_t)L.kb_total * sizeof(fp::KeyBlockRec));
+    m.kb_hi = take(kb_bytes);
+    m.kb_lo = take(kb_bytes);
+    m.total = off;
+    return m;
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -85,6 +116,7 @@ const char *fp_status_string(fp_status s) {
         case FP_ERR_UNSUPPORTED: return "unsupported shape (head_dim and block must be 128, at most 4096 blocks per sequence)";
         case FP_ERR_DEVICE: return "HIP device error";
         case FP_ERR_NOMEM: return "out of host memory";
+        case FP_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned (see fp_workspace_bytes)";
     }
     return "unknown status";
 }
@@ -99,28 +131,36 @@ fp_status fp_layout(const fp_shape *shape, int32_t *m_total, int32_t *n_max, int
     return FP_OK;
 }
 
+size_t fp_workspace_bytes(const fp_shape *shape) {
+    Layout L;
+    if (check_shape(shape, &L) != FP_OK) return 0;
+    return workspace_map(L, shape->hkv).total;
+}
+
 void fp_plan_destroy(fp_plan *p) {
     if (p == nullptr) return;
-    int prev = 0;
-    const bool have_prev = hipGetDevice(&prev) == hipSuccess;
-    if (hipSetDevice(p->device) == hipSuccess) {
-        if (p->d_rows) (void)hipFree(p->d_rows);
-        if (p->d_order) (void)hipFree(p->d_order);
-        if (p->d_rows_ranked) (void)hipFree(p->d_rows_ranked);
-        if (p->d_kblk) (void)hipFree(p->d_kblk);
-        if (p->d_kb_hi) (void)hipFree(p->d_kb_hi);
-        if (p->d_kb_lo) (void)hipFree(p->d_kb_lo);
+    if (p->owns_workspace && p->workspace != nullptr) {
+        int prev = 0;
+        const bool have_prev = hipGetDevice(&prev) == hipSuccess;
+        if (hipSetDevice(p->device) == hipSuccess) (void)hipFree(p->workspace);
+        if (have_prev) (void)hipSetDevice(prev);
     }
-    if (have_prev) (void)hipSetDevice(prev);
     delete p;
 }
 
 fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
+    return fp_plan_create_in(shape, device, nullptr, 0, out);
+}
+
+fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, size_t workspace_bytes, fp_plan **out) {
     if (out == nullptr) return FP_ERR_INVALID_ARG;
     *out = nullptr;
     Layout L;
     const fp_status st = check_shape(shape, &L);
     if (st != FP_OK) return st;
+    const WorkspaceMap wm = workspace_map(L, shape->hkv);
+    if (workspace != nullptr && (workspace_bytes < wm.total || reinterpret_cast<uintptr_t>(workspace) % kWsAlign != 0))
+        return FP_ERR_WORKSPACE;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return FP_ERR_DEVICE;
 
@@ -155,7 +195,8 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
             rec.kb_row0 = L.kb_offset[s];
             rec.k_tok0 = cuk[s];
             rec.k_end = cuk[s + 1];
-            rec.pad0 = rec.pad1 = 0;
+            rec.n_kb = L.kb_offset[s + 1] - L.kb_offset[s];
+            rec.pad1 = 0;
             rows[(size_t)r] = rec;
         }
         for (int j = L.kb_offset[s]; j < L.kb_offset[s + 1]; ++j) {
@@ -175,13 +216,21 @@ fp_status fp_plan_create(const fp_shape *shape, int device, fp_plan **out) {
     int prev = 0;
     (void)hipGetDevice(&prev);
     bool ok = hipSetDevice(device) == hipSuccess;
-    const size_t kb_bytes = (size_t)L.kb_total * p->hkv * fp::kHeadDim * sizeof(uint16_t);
-    ok = ok && hipMalloc(&p->d_rows, rows.size() * sizeof(fp::RowRec)) == hipSuccess;
-    ok = ok && hipMalloc(&p->d_order, order.size() * sizeof(int32_t)) == hipSuccess;
-    ok = ok && hipMalloc(&p->d_rows_ranked, rows.size() * sizeof(fp::RowRec)) == hipSuccess;
-    ok = ok && hipMalloc(&p->d_kblk, kblk.size() * sizeof(fp::KeyBlockRec)) == hipSuccess;
-    ok = ok && hipMalloc(&p->d_kb_hi, kb_bytes) == hipSuccess;
-    ok = ok && hipMalloc(&p->d_kb_lo, kb_bytes) == hipSuccess;
+    if (workspace != nullptr) {
+        p->workspace = workspace;
+    } else {
+        ok = ok && hipMalloc(&p->workspace, wm.total) == hipSuccess;
+        p->owns_workspace = ok;
+    }
+    if (ok) {
+        char *base = static_cast<char *>(p->workspace);
+        p->d_rows = reinterpret_cast<fp::RowRec *>(base + wm.rows);
+        p->d_rows_ranked = reinterpret_cast<fp::RowRec *>(base + wm.rows_ranked);
+        p->d_order = reinterpret_cast<int32_t *>(base + wm.order);
+        p->d_kblk = reinterpret_cast<fp::KeyBlockRec *>(base + wm.kblk);
+        p->d_kb_hi = reinterpret_cast<uint16_t *>(base + wm.kb_hi);
+        p->d_kb_lo = reinterpret_cast<uint16_t *>(base + wm.kb_lo);
+    }
     ok = ok && hipMemcpy(p->d_rows, rows.data(), rows.size() * sizeof(fp::RowRec), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_kblk, kblk.data(), kblk.size() * sizeof(fp::KeyBlockRec), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_order, order.data(), order.size() * sizeof(int32_t), hipMemcpyHostToDevice) == hipSuccess;

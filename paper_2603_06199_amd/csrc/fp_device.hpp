@@ -21,11 +21,11 @@ constexpr float kLog2e = 1.4426950408889634f;
 // One q-block row.  Queries: first token of the block (index into Q and O) and the number of
 // valid tokens in it (1..128).  I = the block's index within its sequence, i.e. its index within
 // the query chunk plus the KV prefix in blocks; its causal key blocks are J <= I.  Keys: the
-// sequence's first token (index into K and V), one past its last, and the first row of its pooled
-// keys in the workspace.
+// sequence's first token (index into K and V), one past its last, the first row of its pooled
+// keys in the workspace and the number of its key blocks.
 struct __attribute__((aligned(16))) RowRec {
     int q_tok0, q_len, I, kb_row0;
-    int k_tok0, k_end, pad0, pad1;
+    int k_tok0, k_end, n_kb, pad1;
 };
 // One key block: first token and number of valid tokens.
 typedef int2 KeyBlockRec;

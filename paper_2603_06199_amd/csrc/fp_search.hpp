@@ -280,9 +280,9 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     for (int J = l; J <= I; J += 64) tot += fast_exp2(ms[J] - Tm);
     tot = wave_sum(tot);
     const float denom = tot + eps * fast_exp2(mtop[hd] - Tm);
-    if (!SELECT) {   // each wave writes half of the columns
+    if (!SELECT) {   // each wave writes half of the sequence's columns; columns past its last key block are left alone
         float *out = scores + ((size_t)h * m_total + r) * n_max;
-        for (int J = l + 64 * qh; J < n_max; J += 128) out[J] = J <= I ? fast_exp2(ms[J] - Tm) / denom : 0.f;
+        for (int J = l + 64 * qh; J < bi.n_kb; J += 128) out[J] = J <= I ? fast_exp2(ms[J] - Tm) / denom : 0.f;
         return;
     }
     // Fused Alg. 2: the normalised scores (the same fp32 expression as above, so the decisions are

@@ -34,7 +34,7 @@ def test_every_declared_symbol_is_exported(lib):
 
 
 def test_status_strings(lib):
-    for s in range(5):
+    for s in range(6):
         assert len(B.status_string(s)) > 0
     assert B.status_string(0) == "ok"
 
@@ -66,6 +66,8 @@ def test_null_arguments(lib):
     assert lib.fp_layout(None, None, None, None) == B.FP_ERR_INVALID_ARG
     s, keep = B.make_shape([0, 128], 4, 1)
     assert lib.fp_plan_create(ctypes.byref(s), 0, None) == B.FP_ERR_INVALID_ARG
+    assert lib.fp_plan_create_in(ctypes.byref(s), 0, None, 0, None) == B.FP_ERR_INVALID_ARG
+    assert lib.fp_workspace_bytes(None) == 0
     for call, nargs in ((lib.fp_block_search, 6), (lib.fp_threshold, 6), (lib.fp_search_select, 8),
                         (lib.fp_sparse_prefill, 9), (lib.fp_dense_prefill, 7)):
         args = [None] * nargs
@@ -82,6 +84,30 @@ def test_plan_create_without_a_gpu_reports_device_error(lib):
     with pytest.raises(B.FlashPrefillError) as e:
         B.Plan([0, 256], 4, 1)
     assert e.value.status == B.FP_ERR_DEVICE
+
+
+def test_workspace_bytes_cover_tables_and_pooled_keys(lib):
+    # three sequences of 3 + 6 + 1 q-blocks = key blocks, Hkv = 2: two 32-byte row records, one rank
+    # entry and one 8-byte key-block record per block, two bf16 planes of pooled keys; each part
+    # rounded up to 256 bytes
+    up = lambda b: (b + 255) // 256 * 256
+    want = 2 * up(10 * 32) + up(10 * 4) + up(10 * 8) + 2 * up(10 * 2 * 128 * 2)
+    assert B.fp_workspace_bytes([0, 300, 1000, 1128], 8, 2) == want
+    # chunked prefill: 3 q-block rows, 5 + 5 key blocks
+    want = 2 * up(3 * 32) + up(3 * 4) + up(10 * 8) + 2 * up(10 * 2 * 128 * 2)
+    assert B.fp_workspace_bytes([0, 200, 328], 8, 2, cu_seqlens_k=[0, 584, 1224]) == want
+    assert B.fp_workspace_bytes([0, 128], 8, 3) == 0            # invalid shape
+    assert B.fp_workspace_bytes([0, 128], 8, 2, head_dim=80) == 0   # unsupported shape
+
+
+def test_caller_workspace_is_checked_before_the_gpu_is_touched(lib):
+    s, keep = B.make_shape([0, 1024], 4, 1)
+    need = lib.fp_workspace_bytes(ctypes.byref(s))
+    h = ctypes.c_void_p()
+    fake = ctypes.c_void_p(0x10000)      # aligned, never dereferenced: the size check comes first
+    assert lib.fp_plan_create_in(ctypes.byref(s), 0, fake, need - 1, ctypes.byref(h)) == B.FP_ERR_WORKSPACE
+    assert lib.fp_plan_create_in(ctypes.byref(s), 0, ctypes.c_void_p(0x10010), need, ctypes.byref(h)) == B.FP_ERR_WORKSPACE
+    assert not h.value
 
 
 def test_largest_supported_sequence_is_accepted(lib):

@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 from paper_2603_06199_amd import binding as B
-from paper_2603_06199_amd import synth
+import synth
 
 from gpu_util import LSE_ATOL, compare_lists_exact, compare_O, dev
 
@@ -56,12 +56,24 @@ def _causal(case):
     return mask
 
 
+def _own(case):
+    """Columns of each row that belong to its own sequence (J < the sequence's key blocks)."""
+    m, n, ro = oracle.layout(case["cuq"], cu_seqlens_k=case["cuk"])
+    own = np.zeros((m, n), bool)
+    for s in range(len(ro) - 1):
+        own[ro[s]:ro[s + 1], :-(-(case["cuk"][s + 1] - case["cuk"][s]) // 128)] = True
+    return own
+
+
 def test_scores(case):
-    P = case["plan"].fp_block_search(case["dQ"], case["dK"])
+    plan = case["plan"]
+    P = torch.full((case["hq"], plan.m_total, plan.n_max), float("nan"), dtype=torch.float32, device="cuda")
+    plan.fp_block_search(case["dQ"], case["dK"], P)
     torch.cuda.synchronize()
     P = P.cpu().numpy()
-    cm = _causal(case)
-    assert not P[:, ~cm].any()
+    cm, own = _causal(case), _own(case)
+    assert not P[:, own & ~cm].any()             # zeros above the diagonal, up to the sequence's last block
+    assert np.isnan(P[:, ~own]).all()            # columns of longer sequences are not written
     np.testing.assert_allclose(P[:, cm], case["P_ref"][:, cm], rtol=5e-4, atol=1e-30)
 
 

@@ -8,7 +8,7 @@ import pytest
 
 import oracle
 from paper_2603_06199_amd import binding as B
-from paper_2603_06199_amd import synth
+import synth
 
 from gpu_util import (BAND, LSE_ATOL, compare_lists_banded, compare_O, compare_scores, dev, row_tokens)
 
@@ -103,33 +103,72 @@ def test_config0_full_layer_against_oracle():
         print(f"{w.name}: density {cnt_h.sum() / (4 * 32 * 33 / 2):.3f}, list mismatches {nd} (band {nb}), sparse O max-abs {mx:.2e}")
 
 
-@pytest.mark.parametrize("cfg,mode", [(1, "coherent"), (3, "coherent"), (3, "literal")])
+@pytest.mark.parametrize("cfg,mode", [(1, "coherent"), (1, "literal"), (2, "coherent"), (2, "literal"),
+                                      (3, "coherent"), (3, "literal")])
 def test_qwen3_shape_sampled_rows(cfg, mode):
-    """Qwen3-30B-A3B attention shape at 32K and 256K tokens: sampled rows against the oracle."""
+    """Qwen3-30B-A3B attention shape at 32K, 128K and 256K tokens: sampled rows against the oracle."""
     w = synth.config(cfg, mode)
     print(f"\n[full size] {w.name}", flush=True)
     r = _run(w)
     n = r["plan"].n_max
     rows_scores = sorted({0, 1, 5, 33, n // 3, n // 2 + 1, n - 2, n - 1})
     if mode == "literal":
-        rows_attn, rows_dense = [0, 3, 37], []          # every causal block is kept: keep the sampled rows short
+        # every causal block is kept: short rows here; the longest row of the headline configuration
+        # has a test of its own below
+        rows_attn, rows_dense = [0, 3, 37], [0, 70]
     else:
         rows_attn, rows_dense = [0, 6, n // 2, n - 1], [0, 70]
     _list_properties(r)
     _sampled_checks(r, rows_scores, rows_attn, rows_dense)
 
 
-def test_llama_varlen_batch_and_alpha_sweep():
+def test_headline_last_row_every_head_dense_and_listed():
+    """Configuration 3 as bench.py runs it (256K tokens, generator as configured): the last q-block
+    row sees all 2048 key blocks, the longest row the kernels ever walk.  Every head of it is
+    compared element by element with the oracle, once through fp_dense_prefill and once through
+    fp_sparse_prefill on the lists the library itself produced."""
+    w = synth.config(3, "literal")
+    print(f"\n[full size] {w.name}: last row, all heads", flush=True)
+    r = _run(w)
+    n = r["plan"].n_max
+    row = [n - 1]
+    toks = row_tokens(r["cu"], row)
+    tt = torch.from_numpy(toks).cuda()
+    idx_h, cnt_h = r["idx"].cpu().numpy(), r["cnt"].cpu().numpy()
+    print(f"listed blocks on the last row per head: min {cnt_h[:, n - 1].min()} max {cnt_h[:, n - 1].max()}", flush=True)
+    Od, lsed = r["plan"].fp_dense_prefill(r["dQ"], r["dK"], r["dV"])
+    torch.cuda.synchronize()
+    Od_ref, lsed_ref = oracle.dense_prefill(r["Q"], r["K"], r["V"], r["cu"], rows=row)
+    mx, mean = compare_O(Od[tt].float().cpu().numpy(), Od_ref[toks])
+    np.testing.assert_allclose(lsed[:, tt].cpu().numpy(), lsed_ref[:, toks], atol=LSE_ATOL, rtol=0)
+    print(f"dense last row: max-abs {mx:.2e} mean-abs {mean:.2e}", flush=True)
+    if (cnt_h[:, n - 1] == n).all():
+        # every block is listed on every head: the listed-blocks definition is the dense one (the
+        # oracle's own tests pin that), so the reference need not be computed a second time
+        assert all(np.array_equal(idx_h[h, n - 1], np.arange(n)) for h in range(w.hq))
+        O_ref, lse_ref = Od_ref, lsed_ref
+    else:
+        O_ref, lse_ref = oracle.sparse_prefill(r["Q"], r["K"], r["V"], r["cu"], idx_h, cnt_h, rows=row)
+    mx, mean = compare_O(r["O"][tt].float().cpu().numpy(), O_ref[toks])
+    np.testing.assert_allclose(r["lse"][:, tt].cpu().numpy(), lse_ref[:, toks], atol=LSE_ATOL, rtol=0)
+    print(f"sparse (listed) last row: max-abs {mx:.2e} mean-abs {mean:.2e}", flush=True)
+
+
+@pytest.mark.parametrize("mode", ["coherent", "literal"])
+def test_llama_varlen_batch_and_alpha_sweep(mode):
     """Llama-3-8B shape, packed 4K + 16K + 64K + 128K tokens: sampled rows of every sequence, and the
     0.5x / 1x / 2x threshold sweep (lists nest, density falls, output error vs dense grows)."""
-    w = synth.config(4, "coherent")
+    w = synth.config(4, mode)
     print(f"\n[full size] {w.name}", flush=True)
     r = _run(w)
     ro = r["plan"].row_offset
     rows_scores = sorted({int(ro[s]) for s in range(4)} | {int(ro[s + 1] - 1) for s in range(4)} | {int(ro[2] + 100), int(ro[3] + 517)})
-    rows_attn = [int(ro[0] + 31), int(ro[1] + 64), int(ro[2]), int(ro[3] + 1023)]
+    if mode == "literal":       # every causal block is kept: the sampled attention rows stay short
+        rows_attn, rows_dense = [int(ro[0] + 31), int(ro[1] + 20), int(ro[2]), int(ro[3] + 45)], []
+    else:
+        rows_attn, rows_dense = [int(ro[0] + 31), int(ro[1] + 64), int(ro[2]), int(ro[3] + 1023)], [int(ro[1] + 9), int(ro[3] + 40)]
     _list_properties(r)
-    _sampled_checks(r, rows_scores, rows_attn, [int(ro[1] + 9), int(ro[3] + 40)])
+    _sampled_checks(r, rows_scores, rows_attn, rows_dense)
     plan = r["plan"]
     Od, _ = plan.fp_dense_prefill(r["dQ"], r["dK"], r["dV"])
     prev_cnt, prev_err = None, None

@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 from paper_2603_06199_amd import binding as B
-from paper_2603_06199_amd import synth
+import synth
 
 from gpu_util import dev
 

@@ -6,7 +6,7 @@ import pytest
 
 import oracle
 from paper_2603_06199_amd import binding as B
-from paper_2603_06199_amd import synth
+import synth
 
 from gpu_util import (LSE_ATOL, compare_lists_banded, compare_lists_exact, compare_O, compare_scores, dev, f32)
 
@@ -214,3 +214,39 @@ def test_custom_softmax_scale_and_eps():
     compare_O(O, O_ref)
     np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, atol=LSE_ATOL, rtol=0)
     plan.close()
+
+
+def test_plan_in_a_caller_owned_workspace():
+    """fp_workspace_bytes + fp_plan_create_in: the plan's tables and pooled keys live in a buffer the
+    caller allocated; results are those of a library-allocated plan, nothing is written past the
+    stated size, and a buffer one byte short is refused."""
+    w = synth.small("caller_ws", [1300, 77, 640], 8, 4, seed=5)
+    Q, K, V = synth.make_qkv(w)
+    cu = w.cu_seqlens
+    dQ, dK, dV = dev(Q), dev(K), dev(V)
+    need = B.fp_workspace_bytes(cu, w.hq, w.hkv)
+    assert need > 0
+    guard = 4096
+    buf = torch.full((need + guard,), 0xA5, dtype=torch.uint8, device="cuda")
+    assert buf.data_ptr() % 256 == 0
+    own = B.Plan(cu, w.hq, w.hkv)
+    mine = B.Plan(cu, w.hq, w.hkv, workspace=buf[:need])
+    for plan in (own, mine):
+        plan.res = (plan.fp_block_search(dQ, dK),) + plan.fp_search_select(dQ, dK, 0.12) + plan.fp_dense_prefill(dQ, dK, dV)
+    torch.cuda.synchronize()
+    P0, idx0, cnt0, O0, lse0 = own.res
+    P1, idx1, cnt1, O1, lse1 = mine.res
+    cm = torch.from_numpy(np.broadcast_to(causal_mask_np(cu), P0.shape).copy()).cuda()
+    assert torch.equal(P0[cm], P1[cm]) and torch.equal(cnt0, cnt1) and torch.equal(O0, O1) and torch.equal(lse0, lse1)
+    valid = torch.arange(idx0.shape[2], device="cuda")[None, None, :] < cnt0[:, :, None]
+    assert torch.equal(idx0[valid], idx1[valid])
+    assert bool((buf[need:] == 0xA5).all())
+    with pytest.raises(B.FlashPrefillError) as e:
+        B.Plan(cu, w.hq, w.hkv, workspace=buf[:need - 1])
+    assert e.value.status == B.FP_ERR_WORKSPACE
+    own.close(); mine.close()
+
+
+def causal_mask_np(cu):
+    from gpu_util import causal_mask
+    return causal_mask(cu)[None]

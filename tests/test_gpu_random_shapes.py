@@ -6,7 +6,7 @@ import pytest
 
 import oracle
 from paper_2603_06199_amd import binding as B
-from paper_2603_06199_amd import synth
+import synth
 
 from gpu_util import BAND, LSE_ATOL, compare_lists_exact, compare_O, dev, lists_to_mask
 
@@ -44,13 +44,16 @@ def test_random_shape(seed):
     dQ, dK, dV = dev(Q), dev(K), dev(V)
     tau_o = None if tau == 0.0 else tau
     P_ref = oracle.block_search(Q, K, cuq, tau=tau_o, cu_seqlens_k=ck)
-    P = plan.fp_block_search(dQ, dK); torch.cuda.synchronize(); Pg = P.cpu().numpy()
     m, n, ro = oracle.layout(cuq, cu_seqlens_k=ck)
-    cm = np.zeros((m, n), bool)
+    P = torch.full((hq, m, n), float("nan"), dtype=torch.float32, device="cuda")
+    plan.fp_block_search(dQ, dK, P); torch.cuda.synchronize(); Pg = P.cpu().numpy()
+    cm, own = np.zeros((m, n), bool), np.zeros((m, n), bool)
     for s in range(nseq):
         pb = (kv_lens[s] - q_lens[s]) // 128
+        own[ro[s]:ro[s + 1], :-(-kv_lens[s] // 128)] = True
         for I in range(ro[s + 1] - ro[s]): cm[ro[s] + I, :I + pb + 1] = True
-    assert not Pg[:, ~cm].any()
+    assert not Pg[:, own & ~cm].any() and np.isnan(Pg[:, ~own]).all()   # zeros up to the sequence's last block, nothing beyond
+    P = torch.nan_to_num(P, nan=0.0)
     np.testing.assert_allclose(Pg[:, cm], P_ref[:, cm], rtol=5e-4, atol=1e-30)
     idx_r, cnt_r = oracle.threshold(P_ref, cuq, alpha, sink_tokens=sink, window_tokens=win, cu_seqlens_k=ck)
     idx, cnt = plan.fp_threshold(torch.from_numpy(P_ref).cuda(), alpha, sink_tokens=sink, window_tokens=win); torch.cuda.synchronize()

@@ -5,7 +5,7 @@ import torch
 from scipy.special import logsumexp, softmax
 
 import oracle
-from paper_2603_06199_amd import synth
+import synth
 
 LOG2E = 1.4426950408889634
 

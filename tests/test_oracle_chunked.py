@@ -7,7 +7,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2603_06199_amd import synth
+import synth
 
 torch = pytest.importorskip("torch")
 

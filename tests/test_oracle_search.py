@@ -8,7 +8,7 @@ import pytest
 from scipy.special import logsumexp, softmax
 
 import oracle
-from paper_2603_06199_amd import synth
+import synth
 
 
 def _f64(bits):
@@ -150,3 +150,40 @@ def test_pooled_probe_lower_bounds_block_mass():
     gm = np.exp(tau * (_f64(K)[:, 0].reshape(4, 128, 16).mean(axis=1) @ q))
     np.testing.assert_allclose(probe, gm / gm.sum(), rtol=1e-5)
     assert np.all(gm <= mass * (1 + 1e-12))
+
+
+@pytest.mark.parametrize("seqlens,hq,hkv,d,block,eps", [
+    ([24], 2, 2, 16, 1, 5.0),            # block = 1: P_IJ = exp(x_J - M) / (sum_K exp(x_K - M) + eps)
+    ([512], 2, 1, 32, 128, 5.0),
+    ([300, 130], 4, 2, 16, 64, 0.75),    # packed, ragged tails
+])
+def test_visible_eps_enters_the_denominator_after_the_rescale_to_the_row_max(seqlens, hq, hkv, d, block, eps):
+    # Eq. 3-4 with an eps that is not a rounding no-op.  After the rescale to M_I = max_{i,J} x_iJ
+    # the row's un-normalised entries are S'_IJ = sum_i exp(x_iJ - M_I) and their total is
+    # T_I = sum_{i,J} exp(x_iJ - M_I) >= 1, so P_IJ = S'_IJ / (T_I + eps): the row sums to
+    # T_I / (T_I + eps) and equals the eps-free softmax scaled by that factor.  An eps applied
+    # before the rescale, to each pair's own sum, or to a differently referenced total fails this.
+    Q, K, _ = synth.random_qkv(seqlens, hq, hkv, d, seed=21, scale=1.5)
+    cu = np.concatenate([[0], np.cumsum(seqlens)])
+    tau = 0.41
+    P = oracle.block_search(Q, K, cu, tau=tau, block=block, eps=eps)
+    Qf, Kf = _f64(Q), _f64(K)
+    g = hq // hkv
+    _, _, ro = synth.layout(cu, block)
+    saw_visible = False
+    for s in range(len(seqlens)):
+        a, b = cu[s], cu[s + 1]
+        nb = ro[s + 1] - ro[s]
+        for h in range(hq):
+            kbar = np.stack([Kf[a + J * block:min(a + (J + 1) * block, b), h // g].mean(axis=0) for J in range(nb)])
+            for I in range(nb):
+                q = Qf[a + I * block:min(a + (I + 1) * block, b), h]
+                x = tau * (q @ kbar[:I + 1].T)
+                T_I = np.exp(logsumexp(x) - x.max())            # library log-sum-exp over every (i, J) of the row
+                assert T_I >= 1.0
+                f = T_I / (T_I + eps)
+                saw_visible |= f < 0.9
+                row = P[h, ro[s] + I, :I + 1].astype(np.float64)
+                np.testing.assert_allclose(row.sum(), f, rtol=2e-6)
+                np.testing.assert_allclose(row, softmax(logsumexp(x, axis=0)) * f, rtol=3e-6, atol=1e-30)
+    assert saw_visible

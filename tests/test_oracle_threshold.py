@@ -5,7 +5,7 @@ import numpy as np
 import pytest
 
 import oracle
-from paper_2603_06199_amd import synth
+import synth
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "threshold_worked_example.txt")
 

@@ -8,7 +8,7 @@ from scipy.special import softmax
 
 import oracle
 from oracle import variants as V
-from paper_2603_06199_amd import synth
+import synth
 
 
 def _bits(x):

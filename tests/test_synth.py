@@ -5,7 +5,7 @@ import pytest
 
 import oracle
 from paper_2603_06199_amd import binding as B
-from paper_2603_06199_amd import synth
+import synth
 
 
 def test_bf16_rounding_is_round_to_nearest_even():
