@@ -90,7 +90,7 @@ const char *fp_status_string(fp_status s);
 fp_status fp_layout(const fp_shape *shape, int32_t *m_total, int32_t *n_max, int32_t *row_offset);
 
 /* Bytes of device memory a plan for `shape` needs (row tables + the pooled keys of Alg. 1 stage 1:
- * 2 x (key blocks) x Hkv x 128 bf16); 0 if the shape is invalid or unsupported.  Host only. */
+ * 2 x (key blocks) x Hkv x 128 bf16 plus two norms per pooled key); 0 if the shape is invalid or unsupported.  Host only. */
 size_t fp_workspace_bytes(const fp_shape *shape);
 
 /* Validates `shape`, selects `device`, allocates one device buffer of fp_workspace_bytes(shape)

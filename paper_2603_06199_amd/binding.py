@@ -166,7 +166,8 @@ class Plan:
         q = _dev_ptr(Q, torch.bfloat16, (self.T, self.hq, self.head_dim), "Q")
         k = _dev_ptr(K, torch.bfloat16, (self.Tk, self.hkv, self.head_dim), "K")
         if scores is None:
-            scores = torch.empty((self.hq, self.m_total, self.n_max), dtype=torch.float32, device=Q.device)
+            # zero-filled: the library leaves the columns past a sequence's own last key block alone
+            scores = torch.zeros((self.hq, self.m_total, self.n_max), dtype=torch.float32, device=Q.device)
         s = _dev_ptr(scores, torch.float32, (self.hq, self.m_total, self.n_max), "scores")
         _check(lib().fp_block_search(self._h, q, k, float(eps), s, _stream_ptr(stream)), "fp_block_search")
         return scores

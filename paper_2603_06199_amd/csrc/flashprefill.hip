@@ -72,6 +72,7 @@ struct fp_plan {
     fp::KeyBlockRec *d_kblk = nullptr;     // [kb_total]
     uint16_t *d_kb_hi = nullptr;      // [kb_total, hkv, 128] bf16
     uint16_t *d_kb_lo = nullptr;
+    float2 *d_kb_norm = nullptr;      // [kb_total, hkv] (|pooled key|, |its lo plane|)
     void *workspace = nullptr;        // the one device buffer all of the above are carved from
     bool owns_workspace = false;      // true: allocated by fp_plan_create, freed by fp_plan_destroy
     size_t search_lds = 0;
@@ -84,7 +85,7 @@ namespace {
 // key-block records and the two pooled-key planes, each part starting on a 256-byte boundary.
 constexpr size_t kWsAlign = 256;
 struct WorkspaceMap {
-    size_t rows = 0, rows_ranked = 0, order = 0, kblk = 0, kb_hi = 0, kb_lo = 0, total = 0;
+    size_t rows = 0, rows_ranked = 0, order = 0, kblk = 0, kb_hi = 0, kb_lo = 0, kb_norm = 0, total = 0;
 };
 WorkspaceMap workspace_map(const Layout &L, int hkv) {
     WorkspaceMap m;
@@ -101,6 +102,7 @@ WorkspaceMap workspace_map(const Layout &L, int hkv) {
     m.kblk = take((size_t)L.kb_total * sizeof(fp::KeyBlockRec));
     m.kb_hi = take(kb_bytes);
     m.kb_lo = take(kb_bytes);
+    m.kb_norm = take((size_t)L.kb_total * hkv * sizeof(float2));
     m.total = off;
     return m;
 }
@@ -178,7 +180,7 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
     const float tau = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
     p->c = tau * fp::kLog2e;
     p->n_pad = (L.n_max + 31) / 32 * 32;
-    p->search_lds = (size_t)fp::kSearchStageBytes + fp::kSearchRowHeader + (size_t)fp::kSearchHeads * p->n_pad * sizeof(float);
+    p->search_lds = (size_t)fp::kSearchStageBytes + fp::kSearchRowHeader + (size_t)fp::kSearchHeads * p->n_pad * sizeof(float) + fp::kSearchCandBytes;
 
     const int32_t *cuk = shape->cu_seqlens_k ? shape->cu_seqlens_k : shape->cu_seqlens;
     std::vector<fp::RowRec> rows((size_t)L.m_total);
@@ -230,6 +232,7 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
         p->d_kblk = reinterpret_cast<fp::KeyBlockRec *>(base + wm.kblk);
         p->d_kb_hi = reinterpret_cast<uint16_t *>(base + wm.kb_hi);
         p->d_kb_lo = reinterpret_cast<uint16_t *>(base + wm.kb_lo);
+        p->d_kb_norm = reinterpret_cast<float2 *>(base + wm.kb_norm);
     }
     ok = ok && hipMemcpy(p->d_rows, rows.data(), rows.size() * sizeof(fp::RowRec), hipMemcpyHostToDevice) == hipSuccess;
     ok = ok && hipMemcpy(p->d_kblk, kblk.data(), kblk.size() * sizeof(fp::KeyBlockRec), hipMemcpyHostToDevice) == hipSuccess;
@@ -237,7 +240,7 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
     ok = ok && hipMemcpy(p->d_rows_ranked, rows_ranked.data(), rows.size() * sizeof(fp::RowRec), hipMemcpyHostToDevice) == hipSuccess;
     // The dynamic-LDS ceilings are per kernel, not per plan: they are set to what the largest
     // supported shape needs, so that plans of different sizes can be alive together.
-    const int search_lds_max = fp::kSearchStageBytes + fp::kSearchRowHeader + fp::kSearchHeads * kMaxBlocksPerSeq * (int)sizeof(float);
+    const int search_lds_max = fp::kSearchStageBytes + fp::kSearchRowHeader + fp::kSearchHeads * kMaxBlocksPerSeq * (int)sizeof(float) + fp::kSearchCandBytes;
     const int thr_lds_max = fp::kThresholdWaves * kMaxBlocksPerSeq * (int)sizeof(float);
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, search_lds_max) == hipSuccess;
@@ -271,22 +274,28 @@ static bool on_plan_device(const fp_plan *p) {
 
 // Alg. 1 stage 1 and stages 2-3; `sel` non-null selects the variant that applies Alg. 2 in place.
 static fp_status launch_search(fp_plan *p, const void *Q, const void *K, float eps, float *scores,
-                               const fp::SelectArgs *sel, void *hip_stream) {
+                               const fp::SelectArgs *sel, void *hip_stream, uint16_t *kb_hi = nullptr,
+                               uint16_t *kb_lo = nullptr, float2 *kb_norm = nullptr) {
     if (!on_plan_device(p)) return FP_ERR_DEVICE;
+    if (kb_hi == nullptr) {   // the plan's own pooled-key planes
+        kb_hi = p->d_kb_hi;
+        kb_lo = p->d_kb_lo;
+        kb_norm = p->d_kb_norm;
+    }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     fp::pool_k_kernel<<<dim3(p->kb_total, p->hkv), 256, 0, st>>>(static_cast<const uint16_t *>(K), p->d_kblk, p->hkv,
-                                                                  p->d_kb_hi, p->d_kb_lo);
+                                                                  p->c, kb_hi, kb_lo, kb_norm);
     const int nchunk = (p->g + fp::kSearchHeads - 1) / fp::kSearchHeads;
     const dim3 grid(p->m_total * p->hkv * nchunk);
     const uint16_t *q = static_cast<const uint16_t *>(Q);
     if (sel != nullptr)
-        fp::search_kernel<true><<<grid, 256, p->search_lds, st>>>(q, p->d_kb_hi, p->d_kb_lo, p->d_rows_ranked, p->d_order,
+        fp::search_kernel<true><<<grid, 256, p->search_lds, st>>>(q, kb_hi, kb_lo, kb_norm, p->d_rows_ranked, p->d_order,
                                                                   p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
-                                                                  p->c, eps, nullptr, *sel);
+                                                                  eps, nullptr, *sel);
     else
-        fp::search_kernel<false><<<grid, 256, p->search_lds, st>>>(q, p->d_kb_hi, p->d_kb_lo, p->d_rows_ranked, p->d_order,
+        fp::search_kernel<false><<<grid, 256, p->search_lds, st>>>(q, kb_hi, kb_lo, kb_norm, p->d_rows_ranked, p->d_order,
                                                                    p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
-                                                                   p->c, eps, scores, fp::SelectArgs{});
+                                                                   eps, scores, fp::SelectArgs{});
     return launch_status();
 }
 

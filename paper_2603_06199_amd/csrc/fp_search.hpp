@@ -8,13 +8,18 @@ namespace fp {
 // ---------------------------------------------------------------------------------------------
 // Alg. 1 stage 1.  One workgroup per (key block, KV head): 128 keys x 128 dims are read once,
 // coalesced (16 lanes cover one 256-byte key row), summed in fp32 and reduced through LDS.
-// The mean is stored as two bf16 planes, hi = bf16(mean) and lo = bf16(mean - hi), so that the
-// score kernel can feed it to bf16 MFMA twice and keep ~16 mantissa bits of the pooled key.
+// The mean is multiplied by c = tau*log2(e) here, once per pooled key, so that the score kernel's
+// products come out as base-2 logits, and stored as two bf16 planes, hi = bf16(c*mean) and
+// lo = bf16(c*mean - hi): fed to bf16 MFMA twice they keep ~16 mantissa bits of the pooled key.
+// Next to the planes go two norms per pooled key: |hi + lo|_2 (bounds every logit against it by
+// Cauchy-Schwarz) and |lo|_2 (bounds what a product with the hi plane alone leaves out).
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict__ K,
-                                                     const KeyBlockRec *__restrict__ kblk, int hkv,
-                                                     uint16_t *__restrict__ kb_hi, uint16_t *__restrict__ kb_lo) {
+                                                     const KeyBlockRec *__restrict__ kblk, int hkv, float c,
+                                                     uint16_t *__restrict__ kb_hi, uint16_t *__restrict__ kb_lo,
+                                                     float2 *__restrict__ kb_norm) {
     __shared__ float red[16][kHeadDim + 4];
+    __shared__ float2 nrm[2];
     const int r = blockIdx.x, hk = blockIdx.y;
     const KeyBlockRec bi = kblk[r];
     const int t = threadIdx.x, chunk = t & 15, rg = t >> 4;
@@ -36,13 +41,18 @@ __global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict_
         float s = 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) s += red[i][t];
-        const float mean = s / (float)bi.y;
-        const __bf16 hi = (__bf16)mean;
-        const __bf16 lo = (__bf16)(mean - (float)hi);
+        const float v = (s / (float)bi.y) * c;
+        const __bf16 hi = (__bf16)v;
+        const __bf16 lo = (__bf16)(v - (float)hi);
         const size_t o = ((size_t)r * hkv + hk) * kHeadDim + t;
         kb_hi[o] = __builtin_bit_cast(uint16_t, hi);
         kb_lo[o] = __builtin_bit_cast(uint16_t, lo);
+        const float both = (float)hi + (float)lo;
+        const float n2 = wave_sum(both * both), l2 = wave_sum((float)lo * (float)lo);
+        if ((t & 63) == 0) nrm[t >> 6] = make_float2(n2, l2);
     }
+    __syncthreads();
+    if (t == 0) kb_norm[(size_t)r * hkv + hk] = make_float2(sqrtf(nrm[0].x + nrm[1].x), sqrtf(nrm[0].y + nrm[1].y));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -52,14 +62,27 @@ __global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict_
 // tiles of 32 blocks (hi and lo planes, shared by the four waves): direct global->LDS loads one
 // tile ahead into two swizzled, unpadded buffers.  For each tile a wave computes its 64 x 32
 // logits with 32 MFMAs (2 query sub-tiles x 8 k-slices x {hi, lo}); the result layout puts one
-// pooled key per lane column, so the reduction over the query axis (Eq. 1-2: max, then sum of
-// 2^(x - max)) is in-register plus one lane exchange.  The two waves of a head then merge their
-// (max, sum) pairs through a small LDS mailbox, one step later.  Registers and LDS leave room
-// for two to four workgroups per CU (two at 4096 blocks per sequence, four up to 1000): waves of
-// different workgroups share a SIMD without sharing a barrier, so one's MFMAs overlap the
-// other's reduction.  Each block pair's (m, S) is kept in LDS as one float, m + log2 S; after the
-// last tile the row is brought to a common reference (Eq. 3), normalised (Eq. 4) and written once.
-// Nothing of size L x L/B ever exists.
+// pooled key per lane column, so the reduction over the query axis (Eq. 1-2) is in-register plus
+// one lane exchange.  The two waves of a head then merge their results through a small LDS
+// mailbox, one step later.  Each block pair's (m, S) is kept in LDS as one float,
+// t = m + log2 S = log2 sum_i 2^x_i; after the last tile the row is brought to a common
+// reference (Eq. 3), normalised (Eq. 4) and written once.  Nothing of size L x L/B ever exists.
+//
+// Two forms of the reduction.  Eq. 1-2 take the pair's max first so that the exponentials cannot
+// overflow.  When every logit of the row is known to be small, |x| <= max_i|q_i| * max_J|kbar_J|
+// < 100 (Cauchy-Schwarz on norms the kernel has anyway), 2^x cannot overflow or underflow in
+// fp32, the max is not needed as a reference and t = log2 sum_i 2^x_i is taken directly: one
+// exponential and one add per logit instead of max, subtract, exponential, add.  The pair's max
+// is also what Eq. 4's eps is scaled against, so this form is taken only when eps is too small
+// to change an fp32 result (the row total is >= 1).  Otherwise, and on ragged q-blocks, the
+// kernel follows Eq. 1-2 literally.
+//
+// SELECT (search + selection in one pass) runs long rows on the hi plane alone, which halves
+// the MFMA work and leaves each t_J with an error of at most eps_J = max_i|q_i| * |lo_J|, then
+// re-scores exactly (both planes, the same instruction sequence as the plain kernel) the few
+// block pairs on which a decision could hinge: those that may hold the row max, and those whose
+// interval [t_J - eps_J, t_J + eps_J] straddles the threshold.  Every other pair is decided with
+// a margin, so the lists are those of exact scores.
 // ---------------------------------------------------------------------------------------------
 constexpr int kSearchPlane = 32 * 256;                 // one plane (hi or lo) of a 32-row tile, unpadded
 constexpr int kSearchTile = 2 * kSearchPlane;          // hi + lo
@@ -67,10 +90,15 @@ constexpr int kSearchBufs = 2;
 constexpr int kSearchHeads = 2;                        // query heads per workgroup
 constexpr int kSearchMailbox = 2 * kSearchHeads * 32 * 8;   // [step parity][head][pooled key] (max, sum)
 constexpr int kSearchStageBytes = kSearchBufs * kSearchTile + kSearchMailbox;
-constexpr int kSearchRowHeader = 16;                   // per-head row maxima, ahead of the rows
+constexpr int kSearchRowHeader = 64;                   // per-head row maxima and prologue exchange, ahead of the rows
+constexpr int kSearchCandBytes = kSearchHeads * (32 + 4) * 4;   // SELECT: candidate tile indices + count per head
+constexpr float kSearchSafeLogit = 100.f;              // |x| below this: 2^x needs no reference point in fp32
+constexpr float kSearchEpsNoop = 0x1p-26f;             // eps below this cannot change an fp32 row total >= 1
+constexpr int kSearchExactTiles = 8;                   // SELECT: rows of up to this many tiles run both planes throughout
 
-// 64 x 32 logits of one pooled-key tile: acc[qt] = Q[qt] (hi + lo)^T.  baddr = buffer base + the
-// lane's row and swizzled chunk for k-slice 0 (slice ks sits at baddr ^ (ks << 5)).
+// 64 x 32 logits of one pooled-key tile: acc[qt] = Q[qt] (hi + lo)^T, or Q[qt] hi^T.  baddr =
+// buffer base + the lane's row and swizzled chunk for k-slice 0 (slice ks sits at baddr ^ (ks << 5)).
+template <bool BOTH>
 __device__ __forceinline__ void search_mma(const char *smem, uint32_t baddr, const bf16x8 (&qa)[2][8], f32x16 (&acc)[2]) {
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt)
@@ -80,20 +108,22 @@ __device__ __forceinline__ void search_mma(const char *smem, uint32_t baddr, con
     for (int ks = 0; ks < 8; ++ks) {
         const char *bp = smem + (baddr ^ (uint32_t)(ks << 5));
         const bf16x8 bh = *reinterpret_cast<const bf16x8 *>(bp);
-        const bf16x8 bl = *reinterpret_cast<const bf16x8 *>(bp + kSearchPlane);
         acc[0] = mfma32(qa[0][ks], bh, acc[0]);
         acc[1] = mfma32(qa[1][ks], bh, acc[1]);
-        acc[0] = mfma32(qa[0][ks], bl, acc[0]);
-        acc[1] = mfma32(qa[1][ks], bl, acc[1]);
+        if (BOTH) {
+            const bf16x8 bl = *reinterpret_cast<const bf16x8 *>(bp + kSearchPlane);
+            acc[0] = mfma32(qa[0][ks], bl, acc[0]);
+            acc[1] = mfma32(qa[1][ks], bl, acc[1]);
+        }
     }
 }
 
 // Eq. 1-2 for the 32 pooled keys of a tile over this wave's 64 queries: per lane column, max and
-// sum of 2^(c x - c max); lanes l and l^32 hold the two halves of a column.  Queries at or past
+// sum of 2^(x - max); lanes l and l^32 hold the two halves of a column.  Queries at or past
 // nq (ragged last q-block; q0 = the wave's first query) are left out; a wave with no valid query
 // returns (-inf, 0), which the merge below treats as empty.
 template <bool RAGGED>
-__device__ __forceinline__ float2 search_reduce(f32x16 (&acc)[2], float c, int nq, int q0, int half) {
+__device__ __forceinline__ float2 search_reduce(f32x16 (&acc)[2], int nq, int q0, int half) {
     if (RAGGED) {
 #pragma unroll
         for (int qt = 0; qt < 2; ++qt)
@@ -109,17 +139,29 @@ __device__ __forceinline__ float2 search_reduce(f32x16 (&acc)[2], float c, int n
         mx = max3(mx, acc[0][i + 1], acc[1][i + 1]);
     }
     mx = halves_max(mx);
-    const float mc = mx * c;
-    const float mcs = RAGGED ? (mx == -INFINITY ? 0.f : mc) : mc;   // all queries missing: every term is 2^-inf = 0
+    const float ms = RAGGED ? (mx == -INFINITY ? 0.f : mx) : mx;   // all queries missing: every term is 2^-inf = 0
     float s0 = 0.f, s1 = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        s0 += fast_exp2(__builtin_fmaf(acc[0][i], c, -mcs));
-        s1 += fast_exp2(__builtin_fmaf(acc[1][i], c, -mcs));
+        s0 += fast_exp2(acc[0][i] - ms);
+        s1 += fast_exp2(acc[1][i] - ms);
     }
     float sum = s0 + s1;
     sum = halves_sum(sum);
-    return make_float2(mc, sum);
+    return make_float2(mx, sum);
+}
+
+// The same sum with reference point 0 (all logits known to be small): (0, sum_i 2^x_i).
+__device__ __forceinline__ float2 search_reduce_small(const f32x16 (&acc)[2]) {
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        s0 += fast_exp2(acc[0][i]);
+        s1 += fast_exp2(acc[1][i]);
+    }
+    float sum = s0 + s1;
+    sum = halves_sum(sum);
+    return make_float2(0.f, sum);
 }
 
 // (max, sum) of the union of two query sets: bring both sums to the common max.
@@ -130,6 +172,27 @@ __device__ __forceinline__ float2 search_merge(float2 a, float2 b) {
     return make_float2(m, sa + sb);
 }
 
+// Largest squared norm among this wave's 64 query rows: each lane holds half of the dims of two
+// rows (the other half is in lane l^32), two bf16 per v_dot2.
+__device__ __forceinline__ float search_qnorm2(const bf16x8 (&qa)[2][8]) {
+    float n2[2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        float a = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; e += 2) {
+                bf16x2 p;
+                p[0] = qa[qt][ks][e];
+                p[1] = qa[qt][ks][e + 1];
+                a = __builtin_amdgcn_fdot2_f32_bf16(p, p, a, false);
+            }
+        n2[qt] = halves_sum(a);
+    }
+    return wave_max(fmaxf(n2[0], n2[1]));
+}
+
 // Selection parameters of the fused variant (Alg. 2 applied to the row while it is still in LDS).
 struct SelectArgs {
     float alpha;
@@ -138,14 +201,15 @@ struct SelectArgs {
 };
 
 template <bool SELECT>
-__global__ __launch_bounds__(256, 4) void search_kernel(
+__global__ __launch_bounds__(256, SELECT ? 3 : 4) void search_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ kb_hi, const uint16_t *__restrict__ kb_lo,
-    const RowRec *__restrict__ rows_ranked, const int32_t *__restrict__ order, int m_total, int n_max, int n_pad,
-    int hq, int hkv, int g, int nchunk, float c /* tau*log2(e) */, float eps, float *__restrict__ scores,
+    const float2 *__restrict__ kb_norm, const RowRec *__restrict__ rows_ranked, const int32_t *__restrict__ order,
+    int m_total, int n_max, int n_pad, int hq, int hkv, int g, int nchunk, float eps, float *__restrict__ scores,
     SelectArgs sel) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
     float2 *mbox = reinterpret_cast<float2 *>(smem + kSearchBufs * kSearchTile);
     float *mtop = reinterpret_cast<float *>(smem + kSearchStageBytes);   // [head] max of the row's pair maxima
+    float *xchg = mtop + 4;                                              // [wave] prologue exchange: query norm, key norm
     float *ms_all = mtop + kSearchRowHeader / sizeof(float);
 
     const int per_row = hkv * nchunk;
@@ -162,6 +226,7 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     const bool active = hg < g;
     const int h = hk * g + (active ? hg : g - 1);
     float *ms = ms_all + (size_t)hd * n_pad;   // the row: t_J = m_J + log2 S_J per block pair
+    const float2 *knorm = kb_norm + (size_t)bi.kb_row0 * hkv + hk;   // pooled key J of the row: knorm[J * hkv]
 
     // Query fragments: qa[qt][ks] covers queries 64qh + 32qt + l%32, dims 16ks + 8(l/32)..+7.
     bf16x8 qa[2][8];
@@ -173,15 +238,22 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) qa[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
     }
+    // Largest pooled-key norm of the row's causal blocks (for the bound on the logits).
+    float kmax = 0.f;
+    for (int J = tid; J <= I; J += 256) kmax = fmaxf(kmax, knorm[(size_t)J * hkv].x);
 
     // Tile loads: 16 wave-wide instructions per tile (2 planes x 8 groups of 4 rows), 4 per wave.
     // Instruction q = 4w + i covers plane q/8, rows 4(q%8) + l/16; lane l fills LDS position l%16
     // of its row, i.e. fetches global chunk (l%16) ^ (row & 15).  Rows past the diagonal
-    // (J > I) are clamped to I: they are computed and dropped.
+    // (J > I) are clamped to I: they are computed and dropped.  A row that runs on the hi plane
+    // alone does not load the other one (waves 2 and 3 then issue nothing).
     const int ntile = I / 32 + 1;
+    const bool ragged = bi.q_len < kBlock;
+    const bool hi_only = SELECT && !ragged && ntile > kSearchExactTiles && sel.alpha > 0.f;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(FP_LDS(char) *)smem;
     const uint32_t row_bytes = (uint32_t)hkv * kHeadDim * 2;
-    const char *pl_base = reinterpret_cast<const char *>(w < 2 ? kb_hi : kb_lo) + ((size_t)bi.kb_row0 * hkv + hk) * kHeadDim * 2;
+    const size_t pl_off = ((size_t)bi.kb_row0 * hkv + hk) * kHeadDim * 2;
+    const char *pl_base = reinterpret_cast<const char *>(w < 2 ? kb_hi : kb_lo) + pl_off;
     int ld_row[4];
     uint32_t ld_col[4];
 #pragma unroll
@@ -191,11 +263,13 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     }
 #define FP_LOAD_TILE(jt)                                                                                  \
     do {                                                                                                  \
-        const uint32_t dst_ = lds_base + (uint32_t)(((jt) % kSearchBufs) * kSearchTile) + (w >> 1) * kSearchPlane; \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                \
-            int J_ = 32 * (jt) + ld_row[i_];                                                              \
-            J_ = J_ <= I ? J_ : I;                                                                        \
-            load_to_lds(pl_base, (uint32_t)J_ * row_bytes + ld_col[i_], dst_ + ((4 * w + i_) & 7) * 1024); \
+        if (!hi_only || w < 2) {                                                                          \
+            const uint32_t dst_ = lds_base + (uint32_t)(((jt) % kSearchBufs) * kSearchTile) + (w >> 1) * kSearchPlane; \
+            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                            \
+                int J_ = 32 * (jt) + ld_row[i_];                                                          \
+                J_ = J_ <= I ? J_ : I;                                                                    \
+                load_to_lds(pl_base, (uint32_t)J_ * row_bytes + ld_col[i_], dst_ + ((4 * w + i_) & 7) * 1024); \
+            }                                                                                             \
         }                                                                                                 \
     } while (0)
 
@@ -205,14 +279,28 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
         (uint32_t)(brow * 256 + ((((brow >> 1) & 7) << 5) | ((half ^ (brow & 1)) << 4)));
 #define FP_BUF(jt) ((uint32_t)(((jt) % kSearchBufs) * kSearchTile))
 
-    // Prologue: tile 0 (and the older Q loads) landed.
+    // Prologue: tile 0 (and the older Q and norm loads) landed; the waves exchange their largest
+    // query norm (per head) and pooled-key norm (per workgroup).
     FP_LOAD_TILE(0);
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qa[qt][ks]));   // Q has landed before the loop
     FP_WAIT_VMCNT(0);
+    {
+        const float qn = sqrtf(search_qnorm2(qa));
+        kmax = wave_max(kmax);
+        if (l == 0) {
+            xchg[2 * w] = qn;
+            xchg[2 * w + 1] = kmax;
+        }
+    }
     __syncthreads();
+    // wave-uniform values, moved to scalar registers so that the branches on them are scalar too
+    const float qnorm = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(fmaxf(xchg[4 * hd], xchg[4 * hd + 2]))));   // the head's 128 queries
+    kmax = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(fmaxf(fmaxf(xchg[1], xchg[3]), fmaxf(xchg[5], xchg[7])))));
+    // small: no logit of this row can leave (-100, 100), and eps is a rounding no-op
+    const bool small = !ragged && qnorm * kmax * 1.01f < kSearchSafeLogit && eps <= kSearchEpsNoop;
 
     // Step jt: tile jt is complete in LDS.  Issue tile jt+1 into the other buffer (its readers,
     // step jt-1's MFMAs, are behind the barrier), compute and reduce tile jt; the upper query half
@@ -220,24 +308,30 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     // its own pair from the previous step and files the result; wait for tile jt+1.
     float2 prev = make_float2(-INFINITY, 0.f);
     float m_top = -INFINITY;
-#define FP_STEP(RAGGED, jt)                                                                               \
+#define FP_FILE(SMALL, Jp_, post_)                                                                        \
+    do {                                                                                                  \
+        if (SMALL) {                                                                                      \
+            ms[Jp_] = __log2f(prev.y + (post_).y);                                                        \
+        } else {                                                                                          \
+            const float2 mg_ = search_merge(prev, (post_));                                               \
+            ms[Jp_] = mg_.x + __log2f(mg_.y);                                                             \
+            m_top = fmaxf(m_top, mg_.x);                                                                  \
+        }                                                                                                 \
+    } while (0)
+#define FP_STEP(RAGGED, SMALL, BOTH, jt)                                                                  \
     do {                                                                                                  \
         const int jt_ = (jt);                                                                             \
         if (jt_ + 1 < ntile) FP_LOAD_TILE(jt_ + 1);                                                       \
         if (active) {                                                                                     \
             f32x16 acc_[2];                                                                               \
-            search_mma(smem, FP_BUF(jt_) + b_frag, qa, acc_);                                             \
-            const float2 v_ = search_reduce<RAGGED>(acc_, c, bi.q_len, 64 * qh, half);                        \
+            search_mma<BOTH>(smem, FP_BUF(jt_) + b_frag, qa, acc_);                                       \
+            const float2 v_ = SMALL ? search_reduce_small(acc_) : search_reduce<RAGGED>(acc_, bi.q_len, 64 * qh, half); \
             if (l < 32) {                                                                                 \
                 if (qh) {                                                                                 \
-                    mbox[((jt_ & 1) * kSearchHeads + hd) * 32 + l] = v_;                                             \
+                    mbox[((jt_ & 1) * kSearchHeads + hd) * 32 + l] = v_;                                  \
                 } else {                                                                                  \
                     const int Jp_ = 32 * (jt_ - 1) + l;                                                   \
-                    if (jt_ > 0 && Jp_ <= I) {                                                            \
-                        const float2 mg_ = search_merge(prev, mbox[(((jt_ - 1) & 1) * kSearchHeads + hd) * 32 + l]); \
-                        ms[Jp_] = mg_.x + __log2f(mg_.y);                                                 \
-                        m_top = fmaxf(m_top, mg_.x);                                                      \
-                    }                                                                                     \
+                    if (jt_ > 0 && Jp_ <= I) FP_FILE(SMALL, Jp_, mbox[(((jt_ - 1) & 1) * kSearchHeads + hd) * 32 + l]); \
                     prev = v_;                                                                            \
                 }                                                                                         \
             }                                                                                             \
@@ -246,27 +340,141 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
         __syncthreads();                                                                                  \
     } while (0)
 
-    if (bi.q_len < kBlock) {
-        for (int jt = 0; jt < ntile; ++jt) FP_STEP(true, jt);
+    if (ragged) {
+        for (int jt = 0; jt < ntile; ++jt) FP_STEP(true, false, true, jt);
+    } else if (hi_only) {
+        if (small) {
+            for (int jt = 0; jt < ntile; ++jt) FP_STEP(false, true, false, jt);
+        } else {
+            for (int jt = 0; jt < ntile; ++jt) FP_STEP(false, false, false, jt);
+        }
+    } else if (small) {
+        for (int jt = 0; jt < ntile; ++jt) FP_STEP(false, true, true, jt);
     } else {
-        for (int jt = 0; jt < ntile; ++jt) FP_STEP(false, jt);
+        for (int jt = 0; jt < ntile; ++jt) FP_STEP(false, false, true, jt);
     }
-#undef FP_LOAD_TILE
-#undef FP_BUF
 #undef FP_STEP
     // the last tile's merge (its post is behind the loop's final barrier), then everyone meets once
-    // more so that both waves of a head see the complete (m, S) row
+    // more so that both waves of a head see the complete row
     if (active && qh == 0) {
         const int Jp = 32 * (ntile - 1) + l;
-        if (l < 32 && Jp <= I) {
-            const float2 mg = search_merge(prev, mbox[(((ntile - 1) & 1) * kSearchHeads + hd) * 32 + l]);
-            ms[Jp] = mg.x + __log2f(mg.y);
-            m_top = fmaxf(m_top, mg.x);
-        }
+        if (l < 32 && Jp <= I) FP_FILE(small, Jp, mbox[(((ntile - 1) & 1) * kSearchHeads + hd) * 32 + l]);
         m_top = wave_max(m_top);
         if (l == 0) mtop[hd] = m_top;
     }
     __syncthreads();
+
+    // ------------------------------------------------------------------------------------------
+    // SELECT on the hi plane: exact re-scoring of the pairs a decision could hinge on.
+    // With eps_J >= |t_J(hi) - t_J(exact)|:  T_lo = max_J (t_J - eps_J) <= T <= T_hi = max_J (t_J + eps_J);
+    // a pair is a candidate if it may hold the row max (t_J + eps_J >= T_lo) or if it is not kept
+    // anyway (sink, window) and its interval meets [T_lo + log2 alpha, T_hi + log2 alpha].  The
+    // scanning wave of each head (its lower query half) collects up to 32 candidates per pass, in
+    // ascending order; the head's two waves gather those pooled keys (both planes) into the head's
+    // tile buffer and run the plain kernel's instruction sequence on them; the exact t_J replaces
+    // the approximate one.  The pass count is uniform over the workgroup (the heads' candidate counts meet in
+    // LDS), so every wave takes the same barriers.
+    // ------------------------------------------------------------------------------------------
+    float T_exact = -INFINITY;   // scanning wave: max of the re-scored t_J
+    if (SELECT && hi_only) {
+        int32_t *cand = reinterpret_cast<int32_t *>(ms_all + (size_t)kSearchHeads * n_pad) + hd * 36;   // [32] indices, [32] = count
+        const float la = __log2f(sel.alpha);
+        float lo_t = -INFINITY, hi_t = -INFINITY;
+        // eps_J = qn |lo_J| + slack; the slack stands for the fp32 accumulation noise of the two
+        // instruction sequences (one plane, two planes), which scales with the size of the logits
+        const float qn = qnorm * 1.004f;
+        const float slack = 0x1p-15f + 0x1p-18f * qnorm * kmax;
+        if (active && qh == 0) {
+            for (int J = l; J <= I; J += 64) {
+                const float tj = ms[J];
+                const float ej = qn * knorm[(size_t)J * hkv].y + slack;
+                lo_t = fmaxf(lo_t, tj - ej);
+                hi_t = fmaxf(hi_t, tj + ej);
+            }
+            lo_t = wave_max(lo_t);
+            hi_t = wave_max(hi_t);
+        }
+        const float thr_lo = lo_t + la - 0x1p-14f, thr_hi = hi_t + la + 0x1p-14f;
+        int J_scan = 0;
+        for (;;) {
+            if (qh == 0) {
+                int have = 0, first = 0;
+                if (active) {
+                    while (J_scan <= I && have < 32) {
+                        const int J = J_scan + l;
+                        bool c = false;
+                        if (J <= I) {
+                            const float tj = ms[J];
+                            const float ej = qn * knorm[(size_t)J * hkv].y + slack;
+                            const bool structural = (J < sel.sinkB) || (I - J < sel.winB);
+                            c = (tj + ej >= lo_t) || (!structural && tj + ej >= thr_lo && tj - ej <= thr_hi);
+                        }
+                        const unsigned long long bal = __ballot(c);
+                        const int slot = have + __builtin_popcountll(bal & ((1ull << l) - 1ull));
+                        if (c && slot < 32) cand[slot] = J;
+                        const int found = __builtin_popcountll(bal);
+                        if (have == 0 && found > 0) first = J_scan + __builtin_ctzll(bal);
+                        if (have + found > 32) {
+                            // the tile is full inside this chunk: resume right after the last index taken
+                            unsigned long long b = bal;
+                            for (int k = have; k < 31; ++k) b &= b - 1;   // drop the (32 - have - 1) lowest set bits
+                            J_scan += __builtin_ctzll(b) + 1;
+                            have = 32;
+                        } else {
+                            have += found;
+                            J_scan += 64;
+                        }
+                    }
+                    if (l >= have && l < 32) cand[l] = first;   // pad the tile with a valid row
+                }
+                if (l == 0) cand[32] = have;
+            }
+            __syncthreads();
+            const int32_t *cand0 = reinterpret_cast<int32_t *>(ms_all + (size_t)kSearchHeads * n_pad);
+            const int n0 = cand0[32], n1 = cand0[36 + 32];
+            if (n0 == 0 && n1 == 0) break;
+            const int nmine = hd ? n1 : n0;
+            if (nmine > 0) {   // wave qh gathers plane qh of the head's tile: 8 instructions of 4 rows
+                const char *pb = reinterpret_cast<const char *>(qh ? kb_lo : kb_hi) + pl_off;
+                const uint32_t dst = lds_base + (uint32_t)(hd * kSearchTile + qh * kSearchPlane);
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const int row = 4 * i + (l >> 4);
+                    const int J = cand[row];
+                    load_to_lds(pb, (uint32_t)J * row_bytes + (uint32_t)(((l & 15) ^ (row & 15)) * 16), dst + i * 1024);
+                }
+            }
+            FP_WAIT_VMCNT(0);
+            __syncthreads();
+            float2 v = make_float2(-INFINITY, 0.f);
+            if (nmine > 0) {
+                f32x16 acc[2];
+                search_mma<true>(smem, (uint32_t)(hd * kSearchTile) + b_frag, qa, acc);
+                v = small ? search_reduce_small(acc) : search_reduce<false>(acc, bi.q_len, 64 * qh, half);
+                if (qh && l < 32) mbox[hd * 32 + l] = v;
+            }
+            __syncthreads();
+            if (nmine > 0 && qh == 0 && l < nmine) {
+                const float2 post = mbox[hd * 32 + l];
+                float tj;
+                if (small) {
+                    tj = __log2f(v.y + post.y);
+                } else {
+                    const float2 mg = search_merge(v, post);
+                    tj = mg.x + __log2f(mg.y);
+                }
+                ms[cand[l]] = tj;
+                T_exact = fmaxf(T_exact, tj);
+            }
+            // the next pass rewrites cand and the tile buffers: its scan starts after this barrier's
+            // readers are done because the scanning wave itself is the last reader of cand here, and
+            // the gathers of the next pass are issued after the barrier that follows the scan
+        }
+        T_exact = wave_max(T_exact);
+    }
+#undef FP_LOAD_TILE
+#undef FP_BUF
+#undef FP_FILE
     if (!active) return;
     if (SELECT && qh) return;   // the list is compacted by one wave per head
     // Eq. 3-4.  With M the max of the row's pair maxima, S'_J = S_J 2^(m_J - M) and the score is
@@ -274,20 +482,26 @@ __global__ __launch_bounds__(256, 4) void search_kernel(
     // the same ratio is formed relative to T = max_J t_J: S'_J = 2^(t_J - T) * 2^(T - M), i.e.
     // score_J = 2^(t_J - T) / (sum_K 2^(t_K - T) + eps * 2^(M - T)), where M <= T because S_J >= 1.
     float Tm = -INFINITY;
-    for (int J = l; J <= I; J += 64) Tm = fmaxf(Tm, ms[J]);
-    Tm = wave_max(Tm);
+    if (SELECT && hi_only) {
+        Tm = T_exact;   // every pair that can hold the max was re-scored
+    } else {
+        for (int J = l; J <= I; J += 64) Tm = fmaxf(Tm, ms[J]);
+        Tm = wave_max(Tm);
+    }
     float tot = 0.f;
     for (int J = l; J <= I; J += 64) tot += fast_exp2(ms[J] - Tm);
     tot = wave_sum(tot);
-    const float denom = tot + eps * fast_exp2(mtop[hd] - Tm);
+    const float denom = tot + (small ? 0.f : eps * fast_exp2(mtop[hd] - Tm));
     if (!SELECT) {   // each wave writes half of the sequence's columns; columns past its last key block are left alone
         float *out = scores + ((size_t)h * m_total + r) * n_max;
         for (int J = l + 64 * qh; J < bi.n_kb; J += 128) out[J] = J <= I ? fast_exp2(ms[J] - Tm) / denom : 0.f;
         return;
     }
-    // Fused Alg. 2: the normalised scores (the same fp32 expression as above, so the decisions are
-    // those of the two-kernel path) replace the row in LDS; threshold from their max; ballot
-    // compaction as in threshold_kernel below.  Each lane re-reads only what it wrote.
+    // Fused Alg. 2: the normalised scores (the same fp32 expression as above) replace the row in
+    // LDS; threshold from their max; ballot compaction as in threshold_kernel below.  Each lane
+    // re-reads only what it wrote.  On a row that ran on the hi plane, an entry that was not
+    // re-scored lies outside the threshold's uncertainty interval, so comparing its approximate
+    // value gives the decision of the exact one.
     float mx = -INFINITY;
     for (int J = l; J <= I; J += 64) {
         const float p = fast_exp2(ms[J] - Tm) / denom;

@@ -93,6 +93,17 @@ def compare_lists_banded(idx_g, cnt_g, P_ref, cu, alpha, sink_tokens=256, window
     return int(diff.sum()), int(band.sum())
 
 
+def compare_lists_same_outside_band(idx_a, cnt_a, idx_b, cnt_b, P, cm, alpha):
+    """Two lists from the library's own paths (numpy): equal, except that pairs whose score P lies
+    within BAND (relative) of alpha * row max may differ.  cm: causal mask [m, n].  Returns #differences."""
+    ma, mb = lists_to_mask(idx_a, cnt_a), lists_to_mask(idx_b, cnt_b)
+    thr = np.float32(alpha) * np.where(cm[None], P, -np.inf).max(axis=2, keepdims=True)
+    band = (np.abs(P - thr) <= BAND * np.abs(thr)) & cm[None]
+    diff = (ma != mb)
+    assert not np.any(diff & ~band), f"{int((diff & ~band).sum())} differences outside the near-threshold band"
+    return int(diff.sum())
+
+
 def compare_O(O_gpu, O_ref, tok_sel=None):
     a = f32(O_gpu) if not isinstance(O_gpu, np.ndarray) else O_gpu
     if tok_sel is not None:

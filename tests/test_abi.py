@@ -88,13 +88,13 @@ def test_plan_create_without_a_gpu_reports_device_error(lib):
 
 def test_workspace_bytes_cover_tables_and_pooled_keys(lib):
     # three sequences of 3 + 6 + 1 q-blocks = key blocks, Hkv = 2: two 32-byte row records, one rank
-    # entry and one 8-byte key-block record per block, two bf16 planes of pooled keys; each part
+    # entry and one 8-byte key-block record per block, two bf16 planes of pooled keys, two fp32 norms per pooled key; each part
     # rounded up to 256 bytes
     up = lambda b: (b + 255) // 256 * 256
-    want = 2 * up(10 * 32) + up(10 * 4) + up(10 * 8) + 2 * up(10 * 2 * 128 * 2)
+    want = 2 * up(10 * 32) + up(10 * 4) + up(10 * 8) + 2 * up(10 * 2 * 128 * 2) + up(10 * 2 * 8)
     assert B.fp_workspace_bytes([0, 300, 1000, 1128], 8, 2) == want
     # chunked prefill: 3 q-block rows, 5 + 5 key blocks
-    want = 2 * up(3 * 32) + up(3 * 4) + up(10 * 8) + 2 * up(10 * 2 * 128 * 2)
+    want = 2 * up(3 * 32) + up(3 * 4) + up(10 * 8) + 2 * up(10 * 2 * 128 * 2) + up(10 * 2 * 8)
     assert B.fp_workspace_bytes([0, 200, 328], 8, 2, cu_seqlens_k=[0, 584, 1224]) == want
     assert B.fp_workspace_bytes([0, 128], 8, 3) == 0            # invalid shape
     assert B.fp_workspace_bytes([0, 128], 8, 2, head_dim=80) == 0   # unsupported shape

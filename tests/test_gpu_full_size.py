@@ -46,6 +46,26 @@ def _list_properties(r):
     assert bool((structural.sum(dim=2) == want[None, :]).all())
 
 
+def _mask_from_lists(idx, cnt):
+    hq, m, n = idx.shape
+    valid = torch.arange(n, device="cuda")[None, None, :] < cnt[:, :, None]
+    mask = torch.zeros((hq, m, n + 1), dtype=torch.bool, device="cuda")
+    mask.scatter_(2, torch.where(valid, idx, torch.full_like(idx, n)).long(), True)
+    return mask[:, :, :n]
+
+
+def _lists_same_outside_band(idx_a, cnt_a, idx_b, cnt_b, P, alpha):
+    """Every row, on the GPU: the lists of the one-pass entry point (long rows are scored on one
+    bf16 plane and re-scored where a decision could hinge) and of the two calls may differ only on
+    pairs whose score lies within BAND (relative) of alpha * row max.  P holds zeros above the
+    diagonal, so its row max is the causal one."""
+    diff = _mask_from_lists(idx_a, cnt_a) ^ _mask_from_lists(idx_b, cnt_b)
+    thr = alpha * P.max(dim=2, keepdim=True).values
+    outside = diff & ((P - thr).abs() > BAND * thr)
+    assert not bool(outside.any()), f"{int(outside.sum())} differences outside the near-threshold band"
+    return int(diff.sum())
+
+
 def _sampled_checks(r, rows_scores, rows_attn, rows_dense):
     w, cu = r["w"], r["cu"]
     P_ref = oracle.block_search(r["Q"], r["K"], cu, rows=rows_scores)
@@ -58,10 +78,9 @@ def _sampled_checks(r, rows_scores, rows_attn, rows_dense):
     idx_f, cnt_f = r["plan"].fp_search_select(r["dQ"], r["dK"], w.alpha)
     torch.cuda.synchronize()
     compare_lists_banded(idx_f.cpu().numpy(), cnt_f.cpu().numpy(), P_ref, cu, w.alpha, rows=rows_scores)
-    assert torch.equal(cnt_f, r["cnt"])
-    valid = torch.arange(idx_f.shape[2], device="cuda")[None, None, :] < cnt_f[:, :, None]
-    assert bool((idx_f == r["idx"])[valid].all())
-    del idx_f, cnt_f, valid
+    nd = _lists_same_outside_band(idx_f, cnt_f, r["idx"], r["cnt"], r["P"], w.alpha)
+    print(f"{w.name}: one-pass vs two-call lists over all rows: {nd} differing pairs, all inside the near-threshold band")
+    del idx_f, cnt_f
     # sparse attention on the GPU's own lists vs the oracle given the same lists
     idx_h, cnt_h = r["idx"].cpu().numpy(), r["cnt"].cpu().numpy()
     O_ref, lse_ref = oracle.sparse_prefill(r["Q"], r["K"], r["V"], cu, idx_h, cnt_h, rows=rows_attn)
@@ -210,7 +229,7 @@ def test_qwen3_shape_chunked_prefill_sampled_rows():
     assert bool(((idx[:, :, 1:] > idx[:, :, :-1]) | ~valid[:, :, 1:]).all())
     structural = ((idx < 2) | ((I[None, :, None] - idx) < 4)) & valid
     assert bool((structural.sum(dim=2) == 6).all())
-    assert torch.equal(cnt_f, cnt) and bool((idx_f == idx)[valid].all())
+    _lists_same_outside_band(idx_f, cnt_f, idx, cnt, P, w.alpha)
     rows = [0, 17, m - 1]
     P_ref = oracle.block_search(Qc, K, cuq, rows=rows, cu_seqlens_k=cuk)
     Pg = P.cpu().numpy()

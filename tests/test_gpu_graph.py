@@ -37,6 +37,11 @@ def test_layer_captured_in_a_graph_replays_bit_exactly():
     layer()
     torch.cuda.synchronize()
     want = [t.clone() for t in (scores, cnt, O, lse, cnt2, O2, Od)]
+    # columns past a sequence's own last key block are not written by the search: compare the rest
+    ro = plan.row_offset
+    own = torch.zeros((m, n), dtype=torch.bool, device="cuda")
+    for s in range(len(ro) - 1):
+        own[ro[s]:ro[s + 1], :ro[s + 1] - ro[s]] = True
     valid = torch.arange(n, device="cuda")[None, None, :] < cnt[:, :, None]
     want_idx = torch.where(valid, idx, torch.zeros_like(idx))
 
@@ -57,7 +62,9 @@ def test_layer_captured_in_a_graph_replays_bit_exactly():
         g.replay()
         torch.cuda.synchronize()
         got = (scores, cnt, O, lse, cnt2, O2, Od)
-        for a, b in zip(got, want):
+        for k, (a, b) in enumerate(zip(got, want)):
+            if k == 0:
+                a, b = a[:, own], b[:, own]
             assert torch.equal(a, b), f"replay {rep} differs from the eager run"
         assert torch.equal(torch.where(valid, idx, torch.zeros_like(idx)), want_idx)
         assert torch.equal(torch.where(valid, idx2, torch.zeros_like(idx)), want_idx)

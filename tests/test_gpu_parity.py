@@ -216,6 +216,40 @@ def test_custom_softmax_scale_and_eps():
     plan.close()
 
 
+@pytest.mark.parametrize("seqlens,hq,hkv,mode", [
+    ([40000], 4, 2, "coherent"),
+    ([128 * 300 + 5, 128 * 290], 8, 1, "coherent"),     # ragged last q-block of a long row; 4 head pairs per KV head
+    ([36000], 6, 2, "literal"),                          # flat score map: many pairs close to the row max
+])
+def test_one_pass_selection_on_long_rows(seqlens, hq, hkv, mode):
+    """Rows of more than 256 key blocks: fp_search_select scores them on the pooled key's hi plane and
+    re-scores exactly the pairs that may hold the row max or straddle the threshold.  Its lists are
+    held to the same rule as the two-call path (equal to the oracle's outside the near-threshold
+    band) and may differ from the two-call lists only inside that band."""
+    from gpu_util import causal_mask, compare_lists_same_outside_band
+    w = synth.small("long_rows", seqlens, hq, hkv, seed=17, mode=mode)
+    Q, K, _ = synth.make_qkv(w)
+    cu = w.cu_seqlens
+    dQ, dK = dev(Q), dev(K)
+    plan = B.Plan(cu, hq, hkv)
+    P_ref = oracle.block_search(Q, K, cu)
+    P = plan.fp_block_search(dQ, dK)
+    torch.cuda.synchronize()
+    compare_scores(P.cpu().numpy(), P_ref, cu)
+    cm = causal_mask(cu)
+    for alpha, sink, win in ((0.12, 256, 512), (0.5, 0, 128), (1.0, 256, 512), (0.97, 0, 0), (3e-3, 0, 0)):
+        idx2, cnt2 = plan.fp_threshold(P, alpha, sink_tokens=sink, window_tokens=win)
+        idx, cnt = plan.fp_search_select(dQ, dK, alpha, sink_tokens=sink, window_tokens=win)
+        torch.cuda.synchronize()
+        nd, nb = compare_lists_banded(idx.cpu().numpy(), cnt.cpu().numpy(), P_ref, cu, alpha, sink_tokens=sink,
+                                      window_tokens=win)
+        nd2 = compare_lists_same_outside_band(idx.cpu().numpy(), cnt.cpu().numpy(), idx2.cpu().numpy(),
+                                              cnt2.cpu().numpy(), P_ref, cm, alpha)
+        kept = int(cnt.sum())
+        print(f"alpha {alpha} sink {sink} window {win}: kept {kept}, vs oracle {nd} mismatches (band {nb}), vs two calls {nd2}")
+    plan.close()
+
+
 def test_plan_in_a_caller_owned_workspace():
     """fp_workspace_bytes + fp_plan_create_in: the plan's tables and pooled keys live in a buffer the
     caller allocated; results are those of a library-allocated plan, nothing is written past the
