@@ -56,8 +56,12 @@ typedef enum {
                             /* KV prefix that is not a multiple of the block                */
     FP_ERR_DEVICE = 3,      /* HIP runtime error (no device, allocation or launch failure) */
     FP_ERR_NOMEM = 4,       /* host allocation failed                                      */
-    FP_ERR_WORKSPACE = 5    /* caller-supplied workspace too small or not 256-byte aligned */
+    FP_ERR_WORKSPACE = 5,   /* caller-supplied workspace too small or not 256-byte aligned */
+    FP_ERR_STATIC_LIMIT = 6 /* fp_block_search_static: shape beyond the built-in scratch    */
 } fp_status;
+
+/* Size of the library's built-in scratch array (one copy per GPU, held until the process ends). */
+#define FP_STATIC_SCRATCH_BYTES ((8u << 20) + (128u << 10))
 
 typedef struct {
     int32_t nseq;              /* sequences in the packed batch, >= 1                         */
@@ -122,6 +126,22 @@ void fp_plan_destroy(fp_plan *plan);
  * valid keys and leaves out missing queries.
  */
 fp_status fp_block_search(fp_plan *plan, const void *Q, const void *K, float eps, float *scores, void *hip_stream);
+
+/*
+ * fp_block_search for callers that cannot allocate device memory or hand a workspace over: code
+ * under HIP graph capture, tight serving loops that share one scratch area among many plans,
+ * harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as
+ * fp_block_search; the pooled keys of Alg. 1 stage 1 go to a fixed array inside the library
+ * (FP_STATIC_SCRATCH_BYTES per GPU) instead of the plan's buffer, so `plan` may be one whose
+ * workspace is in use elsewhere.  Limit: (key blocks of the batch) x Hkv x (2 planes x 256 B + 8 B
+ * of norms) must fit, i.e. key blocks x Hkv <= 16384 (256K tokens at Hkv = 8, 512K at Hkv = 4); beyond it the call
+ * returns FP_ERR_STATIC_LIMIT and launches nothing.  The call allocates nothing and frees
+ * nothing.  All calls on one GPU share that GPU's array: it needs no clearing (every entry a
+ * call reads it has written first), but two calls that may overlap in time on one GPU (different
+ * streams, or graphs replayed concurrently) race and must be ordered by the caller.
+ */
+fp_status fp_block_search_static(fp_plan *plan, const void *Q, const void *K, float eps, float *scores,
+                                 void *hip_stream);
 
 /*
  * Stage (ii).  Alg. 2: per (head, q-block row): thresh = alpha * max_{J<=I} scores (Sec. 3.4),

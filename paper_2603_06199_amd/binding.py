@@ -14,10 +14,10 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflashprefill.so")
 
-FP_OK, FP_ERR_INVALID_ARG, FP_ERR_UNSUPPORTED, FP_ERR_DEVICE, FP_ERR_NOMEM, FP_ERR_WORKSPACE = range(6)
+FP_OK, FP_ERR_INVALID_ARG, FP_ERR_UNSUPPORTED, FP_ERR_DEVICE, FP_ERR_NOMEM, FP_ERR_WORKSPACE, FP_ERR_STATIC_LIMIT = range(7)
 
 EXPORTS = ("fp_status_string", "fp_layout", "fp_workspace_bytes", "fp_plan_create", "fp_plan_create_in",
-           "fp_plan_destroy", "fp_block_search",
+           "fp_plan_destroy", "fp_block_search", "fp_block_search_static",
            "fp_threshold", "fp_search_select", "fp_sparse_prefill", "fp_dense_prefill")
 
 
@@ -60,6 +60,7 @@ def lib() -> ctypes.CDLL:
         L.fp_plan_destroy.argtypes = [vp]
         L.fp_plan_destroy.restype = None
         L.fp_block_search.argtypes = [vp, vp, vp, f32, vp, vp]
+        L.fp_block_search_static.argtypes = [vp, vp, vp, f32, vp, vp]
         L.fp_threshold.argtypes = [vp, vp, ctypes.POINTER(fp_params), vp, vp, vp]
         L.fp_search_select.argtypes = [vp, vp, vp, f32, ctypes.POINTER(fp_params), vp, vp, vp]
         L.fp_sparse_prefill.argtypes = [vp, vp, vp, vp, vp, vp, vp, vp, vp]
@@ -170,6 +171,15 @@ class Plan:
             scores = torch.zeros((self.hq, self.m_total, self.n_max), dtype=torch.float32, device=Q.device)
         s = _dev_ptr(scores, torch.float32, (self.hq, self.m_total, self.n_max), "scores")
         _check(lib().fp_block_search(self._h, q, k, float(eps), s, _stream_ptr(stream)), "fp_block_search")
+        return scores
+
+    def fp_block_search_static(self, Q, K, scores, eps: float = 1e-10, stream=None):
+        """fp_block_search with the pooled keys in the library's built-in scratch; `scores` is the caller's."""
+        import torch
+        q = _dev_ptr(Q, torch.bfloat16, (self.T, self.hq, self.head_dim), "Q")
+        k = _dev_ptr(K, torch.bfloat16, (self.Tk, self.hkv, self.head_dim), "K")
+        s = _dev_ptr(scores, torch.float32, (self.hq, self.m_total, self.n_max), "scores")
+        _check(lib().fp_block_search_static(self._h, q, k, float(eps), s, _stream_ptr(stream)), "fp_block_search_static")
         return scores
 
     def fp_threshold(self, scores, alpha: float, sink_tokens: int = 256, window_tokens: int = 512, idx=None,

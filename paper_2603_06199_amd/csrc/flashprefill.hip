@@ -6,6 +6,7 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <vector>
@@ -14,7 +15,33 @@
 #include "fp_device.hpp"
 #include "fp_search.hpp"
 
+// Built-in scratch for fp_block_search_static: the two pooled-key planes of one call.  Every GPU the
+// library runs on holds its own copy until the process ends.  In host code the array's name is
+// only a handle for hipGetSymbolAddress; kernels and host calls use the per-device address.
+constexpr size_t kStaticScratchBytes = FP_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void *g_scratch_ptr[kMaxDevices] = {};
+
+// Address of the calling thread's current device's copy of `scratch`; looked up once per device.
+// `device` must be the current device.  Returns nullptr on failure.
+void *static_scratch(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (g_scratch_ptr[device] == nullptr) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) {
+            (void)hipGetLastError();
+            return nullptr;
+        }
+        g_scratch_ptr[device] = ptr;
+    }
+    return g_scratch_ptr[device];
+}
 
 // (m, S) of one row for 2 heads must fit the score kernel's LDS next to its tile buffers
 // (2 x 16 KB + 1 KB + 2 x 8 B x blocks <= 160 KB would allow more; 4096 blocks = 512K tokens)
@@ -118,6 +145,9 @@ const char *fp_status_string(fp_status s) {
         case FP_ERR_UNSUPPORTED: return "unsupported shape (head_dim and block must be 128, at most 4096 blocks per sequence)";
         case FP_ERR_DEVICE: return "HIP device error";
         case FP_ERR_NOMEM: return "out of host memory";
+        case FP_ERR_STATIC_LIMIT:
+            return "shape needs more pooled-key scratch than the library's built-in array holds (fp_block_search_static: "
+                   "key blocks x Hkv <= 16384); use fp_block_search";
         case FP_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned (see fp_workspace_bytes)";
     }
     return "unknown status";
@@ -224,6 +254,7 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
         ok = ok && hipMalloc(&p->workspace, wm.total) == hipSuccess;
         p->owns_workspace = ok;
     }
+    ok = ok && static_scratch(device) != nullptr;   // set-up of the built-in scratch, once per device
     if (ok) {
         char *base = static_cast<char *>(p->workspace);
         p->d_rows = reinterpret_cast<fp::RowRec *>(base + wm.rows);
@@ -306,6 +337,18 @@ static bool params_ok(const fp_params *params) {
 fp_status fp_block_search(fp_plan *p, const void *Q, const void *K, float eps, float *scores, void *hip_stream) {
     if (p == nullptr || Q == nullptr || K == nullptr || scores == nullptr || !(eps >= 0.f)) return FP_ERR_INVALID_ARG;
     return launch_search(p, Q, K, eps, scores, nullptr, hip_stream);
+}
+
+fp_status fp_block_search_static(fp_plan *p, const void *Q, const void *K, float eps, float *scores, void *hip_stream) {
+    if (p == nullptr || Q == nullptr || K == nullptr || scores == nullptr || !(eps >= 0.f)) return FP_ERR_INVALID_ARG;
+    const size_t plane = ((size_t)p->kb_total * p->hkv * fp::kHeadDim * sizeof(uint16_t) + kWsAlign - 1) / kWsAlign * kWsAlign;
+    const size_t norms = (size_t)p->kb_total * p->hkv * sizeof(float2);
+    if (2 * plane + norms > kStaticScratchBytes) return FP_ERR_STATIC_LIMIT;
+    if (!on_plan_device(p)) return FP_ERR_DEVICE;
+    char *base = static_cast<char *>(static_scratch(p->device));
+    if (base == nullptr) return FP_ERR_DEVICE;
+    return launch_search(p, Q, K, eps, scores, nullptr, hip_stream, reinterpret_cast<uint16_t *>(base),
+                         reinterpret_cast<uint16_t *>(base + plane), reinterpret_cast<float2 *>(base + 2 * plane));
 }
 
 fp_status fp_search_select(fp_plan *p, const void *Q, const void *K, float eps, const fp_params *params, int32_t *idx,
