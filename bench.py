@@ -35,11 +35,17 @@ def profiled_traffic(workload_tag, kernel):
     (FETCH_SIZE / WRITE_SIZE scaled by a known-size copy; see profiles/), or None."""
     path = os.path.join(ROOT, "profiles", f"bench_{workload_tag}_hbm_bytes.txt")
     try:
+        measured = "unknown"
         for line in open(path):
+            if line.startswith("measured:"):
+                measured = line.split(":", 1)[1].strip()
             tok = line.split()
             if tok and tok[0] == kernel and len(tok) >= 5:
                 rd, wr = float(tok[-2]) * 2**30, float(tok[-1]) * 2**30
-                return {"bytes": rd + wr, "read_bytes": rd, "write_bytes": wr, "source": os.path.relpath(path, ROOT)}
+                # a stored figure from an earlier profiler run of this command, not of this process:
+                # `measured` names the source revision it was taken at
+                return {"bytes": rd + wr, "read_bytes": rd, "write_bytes": wr, "source": os.path.relpath(path, ROOT),
+                        "measured": measured, "live": False}
     except OSError:
         pass
     return None
@@ -160,6 +166,8 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk
         speedup_vs_own_dense=(dense_ms / float(search_ms + thr_ms + sparse_ms)) if dense_ms else None,
         speedup_vs_own_dense_fused=(dense_ms / float(fused_ms + sparse_ms)) if dense_ms else None,
         search_gbs=search_bytes / search_ms / 1e6,
+        # the one-pass entry point writes lists instead of the score map: Q + K once, 4 B per kept pair and per row
+        search_select_gbs=(2 * 128 * (T * w.hq + plan.Tk * w.hkv) + 4 * kept + 4 * hq * m) / fused_ms / 1e6,
         search_mfma_tflops=pairs * 2 * 128 * 128 * 2 / search_ms / 1e9,   # two bf16 passes (hi, lo) per pair
         search_exp2_per_s=pairs * 128 / (search_ms * 1e-3),                # one exponential per (query, pooled key)
         threshold_gbs=thr_bytes / thr_ms / 1e6,
@@ -328,6 +336,7 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="length sweep 4K..512K on the Qwen3-30B-A3B shape (block-coherent planting): per-stage ms, "
                          "speedup over the own dense kernel, and the sparse kernel alone at forced 60 %% / 6 %% density")
+    ap.add_argument("--lengths", type=int, nargs="*", default=[], help="with --sweep: only these token counts")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -349,10 +358,15 @@ def main():
     if a.sweep:
         import dataclasses
         rows = []
-        for L in (4096, 8192, 16384, 32768, 65536, 131072, 262144, 524288):
+        # densities the paper reports for this model at each length (its density table; real activations)
+        paper_density = {4096: 0.704, 8192: 0.460, 16384: 0.290, 32768: 0.176, 65536: 0.100, 131072: 0.058, 262144: 0.035}
+        for L in (a.lengths or (4096, 8192, 16384, 32768, 65536, 131072, 262144, 524288)):
             wl = dataclasses.replace(synth.config(1, "coherent"), seqlens=(L,), name=f"qwen3_shape_{L // 1024}k_coherent")
             r, h = run_workload(wl, a.steps, a.warmup, dense_runs=2, torch=torch, B=B, min_timed_ms=100.0)
-            r["forced_density"] = [forced_density_run(wl, h, d, r["timed_steps"], torch) for d in (0.6, 0.06)]
+            dens = (0.6, 0.06) + ((paper_density[L],) if L in paper_density else ())
+            r["forced_density"] = [forced_density_run(wl, h, d, r["timed_steps"], torch) for d in dens]
+            r["search_hbm_frac"] = r["search_gbs"] / HBM_PEAK_GBS
+            r["search_select_hbm_frac"] = r["search_select_gbs"] / HBM_PEAK_GBS
             log(f"[bench] sweep {json.dumps(r)}")
             rows.append(r)
             del h

@@ -52,9 +52,11 @@ __device__ __forceinline__ s16x4 lds_read_tr(const char *p) {
  *
  * Work order: blockIdx -> (XCD, slot).  Consecutive workgroup ids land on different XCDs, each
  * with its own L2; slot k of XCD x takes query head k%g of super-item (k/g)*8 + x, where a
- * super-item is (row rank, KV head) and rows are ranked heaviest (largest I) first.  The g query
- * heads that share a KV head, and neighbouring rows of that KV head, therefore run on one XCD
- * at about the same time and find each other's K/V tiles in its L2.
+ * super-item is (KV head, row rank), KV head outermost, and rows are ranked heaviest (largest I)
+ * first.  The g query heads that share a KV head run on one XCD at about the same time and find
+ * each other's K/V tiles in its L2; the eight XCDs work on eight neighbouring rows of the same KV
+ * head, so one head's K and V (128 MiB each at 512K tokens) are what the last-level cache holds
+ * at a time, not every head's.
  */
 template <bool SPARSE>
 __device__ __forceinline__ int attn_tile_block(const int32_t *list, int t, int I) {
@@ -171,7 +173,9 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     const int x = blockIdx.x & 7, k = blockIdx.x >> 3;
     const int s = (k / g) * 8 + x, hg = k % g;
     if (s >= m_total * hkv) return;
-    const int rank = s / hkv, hk = s - rank * hkv;
+    // KV head outermost: the rows of one KV head run together, so the K/V of one head (not of all
+    // heads at once) is what the last-level cache has to hold
+    const int hk = s / m_total, rank = s - hk * m_total;
     const int r = order[rank];               // both tables are indexed by rank: one round trip
     const RowRec bi = rows_ranked[rank];
     const int h = hk * g + hg;
