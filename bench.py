@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
-PAIR_FLOPS = 4 * 128 * 128 * 128  # QK^T + PV of one (q-block, k-block) visit
+PAIR_FLOPS = 4 * 128 * 128 * 128  # QK^T + PV of one (q-block, k-block) visit at head dimension 128 (scaled by d/128 otherwise)
 
 
 def log(*a):
@@ -78,8 +78,10 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk
         Q = np.ascontiguousarray(np.concatenate([Q[cuk[i + 1] - qlen[i]:cuk[i + 1]] for i in range(len(qlen))]))
         cu = np.concatenate([[0], np.cumsum(qlen)]).astype(np.int32)
     dQ, dK, dV = B.to_device_bf16(Q), B.to_device_bf16(K), B.to_device_bf16(V)
-    plan = B.Plan(cu, w.hq, w.hkv, cu_seqlens_k=cuk)
+    plan = B.Plan(cu, w.hq, w.hkv, head_dim=w.head_dim, cu_seqlens_k=cuk)
     hq, m, n = w.hq, plan.m_total, plan.n_max
+    d = w.head_dim
+    pair_flops = PAIR_FLOPS * d // 128
     scores = torch.empty((hq, m, n), dtype=torch.float32, device="cuda")
     idx = torch.empty((hq, m, n), dtype=torch.int32, device="cuda")
     cnt = torch.empty((hq, m), dtype=torch.int32, device="cuda")
@@ -152,7 +154,7 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk
     assert int(cnt.sum().item()) == kept
 
     T = plan.T
-    search_bytes = 2 * 128 * (T * w.hq + plan.Tk * w.hkv) + 4 * pairs   # Q once + K once + one fp32 per causal pair
+    search_bytes = 2 * d * (T * w.hq + plan.Tk * w.hkv) + 4 * pairs   # Q once + K once + one fp32 per causal pair
     thr_bytes = 4 * pairs + 4 * kept + 4 * hq * m
     res = dict(
         workload=w.name, tokens=T, key_tokens=plan.Tk, hq=w.hq, hkv=w.hkv, alpha=w.alpha, planting=w.mode, timed_steps=steps,
@@ -167,12 +169,13 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk
         speedup_vs_own_dense_fused=(dense_ms / float(fused_ms + sparse_ms)) if dense_ms else None,
         search_gbs=search_bytes / search_ms / 1e6,
         # the one-pass entry point writes lists instead of the score map: Q + K once, 4 B per kept pair and per row
-        search_select_gbs=(2 * 128 * (T * w.hq + plan.Tk * w.hkv) + 4 * kept + 4 * hq * m) / fused_ms / 1e6,
-        search_mfma_tflops=pairs * 2 * 128 * 128 * 2 / search_ms / 1e9,   # two bf16 passes (hi, lo) per pair
+        search_select_gbs=(2 * d * (T * w.hq + plan.Tk * w.hkv) + 4 * kept + 4 * hq * m) / fused_ms / 1e6,
+        search_mfma_tflops=pairs * 2 * 128 * d * 2 / search_ms / 1e9,   # two bf16 passes (hi, lo) per pair
         search_exp2_per_s=pairs * 128 / (search_ms * 1e-3),                # one exponential per (query, pooled key)
         threshold_gbs=thr_bytes / thr_ms / 1e6,
-        sparse_tflops=kept * PAIR_FLOPS / sparse_ms / 1e9,
-        dense_tflops=(pairs * PAIR_FLOPS / dense_ms / 1e9) if dense_ms else None,
+        sparse_tflops=kept * pair_flops / sparse_ms / 1e9,
+        dense_tflops=(pairs * pair_flops / dense_ms / 1e9) if dense_ms else None,
+        head_dim=d,
     )
     host = dict(Q=Q, K=K, V=V, cu=cu, idx=idx, cnt=cnt, O=O, scores=scores, plan=plan, dQ=dQ, dK=dK, dV=dV)
     return res, host
@@ -207,7 +210,7 @@ def forced_density_run(w, host, density, steps, torch):
     ms = e0.elapsed_time(e1) / steps
     pairs = causal_pairs(plan.row_offset, hq)
     return dict(target_density=density, density=kept / pairs, sparse_attention_ms=ms,
-                sparse_tflops=kept * PAIR_FLOPS / ms / 1e9)
+                sparse_tflops=kept * (PAIR_FLOPS * w.head_dim // 128) / ms / 1e9)
 
 
 def alpha_sweep(w, host, steps, torch, factors=(0.5, 1.0, 2.0)):
@@ -259,6 +262,15 @@ def library_gemm_tflops(torch, n=8192):
     torch.cuda.synchronize()
     del c
     return 2 * n ** 3 / (e0.elapsed_time(e1) / 50) / 1e9
+
+
+def calibrate_copy(torch):
+    """One plain 1 GiB device copy: a kernel of known size for scaling rocprofv3's byte counters."""
+    src = torch.empty(2**28, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+    torch.cuda.synchronize()
+    del src, dst
 
 
 def cpu_baseline(w, host, res, torch, budget_pairs=16000):
@@ -336,6 +348,8 @@ def main():
     ap.add_argument("--sweep", action="store_true",
                     help="length sweep 4K..512K on the Qwen3-30B-A3B shape (block-coherent planting): per-stage ms, "
                          "speedup over the own dense kernel, and the sparse kernel alone at forced 60 %% / 6 %% density")
+    ap.add_argument("--head-dim", type=int, default=128, choices=[64, 128, 256],
+                    help="head dimension of the synthetic layer (the configurations are stated at 128)")
     ap.add_argument("--lengths", type=int, nargs="*", default=[], help="with --sweep: only these token counts")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
@@ -355,13 +369,14 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
 
+    import dataclasses
     if a.sweep:
-        import dataclasses
         rows = []
         # densities the paper reports for this model at each length (its density table; real activations)
         paper_density = {4096: 0.704, 8192: 0.460, 16384: 0.290, 32768: 0.176, 65536: 0.100, 131072: 0.058, 262144: 0.035}
         for L in (a.lengths or (4096, 8192, 16384, 32768, 65536, 131072, 262144, 524288)):
-            wl = dataclasses.replace(synth.config(1, "coherent"), seqlens=(L,), name=f"qwen3_shape_{L // 1024}k_coherent")
+            wl = dataclasses.replace(synth.config(1, "coherent"), seqlens=(L,), name=f"qwen3_shape_{L // 1024}k_coherent",
+                                     head_dim=a.head_dim)
             r, h = run_workload(wl, a.steps, a.warmup, dense_runs=2, torch=torch, B=B, min_timed_ms=100.0)
             dens = (0.6, 0.06) + ((paper_density[L],) if L in paper_density else ())
             r["forced_density"] = [forced_density_run(wl, h, d, r["timed_steps"], torch) for d in dens]
@@ -371,9 +386,11 @@ def main():
             rows.append(r)
             del h
             torch.cuda.empty_cache()
+        if a.calibrate_copy:
+            calibrate_copy(torch)
         print(json.dumps({"metric": "sparse prefill ms/layer vs length (sweep)", "unit": "ms/layer", "n_gpus": 1,
                           "steps": a.steps, "warmup": a.warmup, "dtype": "bf16", "data": "synthetic",
-                          "config": {"workload": "Qwen3-30B-A3B attention shape (Hq=32, Hkv=4, d=128), block-coherent planting, "
+                          "config": {"workload": f"Qwen3-30B-A3B attention shape (Hq=32, Hkv=4, d={a.head_dim}), block-coherent planting, "
                                                  "alpha=0.12, 4K..512K tokens"},
                           "paper_context": "paper (NVIDIA H20, real activations): speedup vs FlashAttention 1.71/2.79/4.48/6.94/11.45/18.67/27.78x "
                                            "at 4K..256K; densities 70.4/46.0/29.0/17.6/10.0/5.8/3.5 %",
@@ -381,7 +398,7 @@ def main():
         return
 
     if a.chunk > 0:
-        w = synth.config(a.config, a.planting)
+        w = dataclasses.replace(synth.config(a.config, a.planting), head_dim=a.head_dim)
         r, h = run_workload(w, a.steps, a.warmup, dense_runs=2, torch=torch, B=B, min_timed_ms=100.0, chunk=a.chunk)
         del h
         print(json.dumps({"metric": "chunked sparse prefill ms/layer (block search + threshold + block-sparse attention)",
@@ -389,12 +406,12 @@ def main():
                           "warmup": a.warmup, "ms_per_step": r["ms"]["end_to_end"], "higher_is_better": False,
                           "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
                           "config": {"workload": f"{w.name}: last {a.chunk} tokens of each sequence as one prefill chunk, "
-                                                 f"Hq={w.hq} Hkv={w.hkv} d=128, {r['tokens']} query / {r['key_tokens']} key tokens"},
+                                                 f"Hq={w.hq} Hkv={w.hkv} d={w.head_dim}, {r['tokens']} query / {r['key_tokens']} key tokens"},
                           "stages_ms": r["ms"], "density": r["density"], "speedup_vs_own_dense": r["speedup_vs_own_dense"],
                           "sparse_tflops": r["sparse_tflops"], "dense_tflops": r["dense_tflops"]}), flush=True)
         return
 
-    w = synth.config(a.config, a.planting)
+    w = dataclasses.replace(synth.config(a.config, a.planting), head_dim=a.head_dim)
     if a.planting == "coherent":
         a.no_supplementary = True
     res, host = run_workload(w, a.steps, a.warmup, dense_runs=2, torch=torch, B=B)
@@ -418,7 +435,7 @@ def main():
 
     sup = None
     if not a.no_supplementary:
-        ws = synth.config(a.config, "coherent")
+        ws = dataclasses.replace(synth.config(a.config, "coherent"), head_dim=a.head_dim)
         sup, host2 = run_workload(ws, a.steps, a.warmup, dense_runs=0, torch=torch, B=B)
         sup["ms"]["dense"] = dense_ms            # same shape: the dense kernel's time does not depend on values
         sup["speedup_vs_own_dense"] = dense_ms / sup["ms"]["end_to_end"]
@@ -429,11 +446,7 @@ def main():
         del host2
 
     if a.calibrate_copy:
-        src = torch.empty(2**28, dtype=torch.float32, device="cuda").normal_()
-        dst = torch.empty_like(src)
-        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
-        torch.cuda.synchronize()
-        del src, dst
+        calibrate_copy(torch)
 
     e2e = res["ms"]["end_to_end"]
     out = {
@@ -441,7 +454,7 @@ def main():
         "value": e2e, "unit": "ms/layer", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": e2e, "higher_is_better": False, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{w.name}: B=1 Hq={w.hq} Hkv={w.hkv} d=128 S={w.total_tokens} causal bf16, "
+        "config": {"workload": f"{w.name}: B=1 Hq={w.hq} Hkv={w.hkv} d={w.head_dim} S={w.total_tokens} causal bf16, "
                                f"block 128, alpha={w.alpha}, sink 256, window 512, "
                                + ("generator as configured (N(0,1), RoPE 1e6, "
                                   f"{w.n_vert} single-token vertical plants, {w.n_slash} slash lags)" if w.mode == "literal"

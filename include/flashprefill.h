@@ -14,7 +14,7 @@
  *   - Every tensor pointer is a DEVICE pointer owned by the caller; the library never
  *     frees or reallocates it.  `cu_seqlens` inside fp_shape is a HOST pointer, read only
  *     during fp_layout / fp_plan_create.
- *   - Q and O are [T, Hq, d], K and V are [Tk, Hkv, d], bf16, contiguous, token-major;
+ *   - Q and O are [T, Hq, d], K and V are [Tk, Hkv, d] (d = head_dim), bf16, contiguous, token-major;
  *     T = cu_seqlens[nseq], Tk = cu_seqlens_k[nseq].  Sequence s owns query tokens
  *     cu_seqlens[s] .. cu_seqlens[s+1]-1 and key tokens cu_seqlens_k[s] .. cu_seqlens_k[s+1]-1.
  *     Query head h reads KV head h / (Hq / Hkv).
@@ -52,7 +52,7 @@ extern "C" {
 typedef enum {
     FP_OK = 0,
     FP_ERR_INVALID_ARG = 1, /* null pointer, inconsistent shape, bad cu_seqlens            */
-    FP_ERR_UNSUPPORTED = 2, /* head_dim != 128, block != 128, more than 4096 blocks/seq, or a */
+    FP_ERR_UNSUPPORTED = 2, /* head_dim not 64/128/256, block != 128, over 4096 blocks/seq, or a */
                             /* KV prefix that is not a multiple of the block                */
     FP_ERR_DEVICE = 3,      /* HIP runtime error (no device, allocation or launch failure) */
     FP_ERR_NOMEM = 4,       /* host allocation failed                                      */
@@ -67,7 +67,7 @@ typedef struct {
     int32_t nseq;              /* sequences in the packed batch, >= 1                         */
     const int32_t *cu_seqlens; /* HOST, nseq+1 entries, [0] = 0, strictly increasing          */
     int32_t hq, hkv;           /* query heads, KV heads; hq % hkv == 0                        */
-    int32_t head_dim;          /* 128                                                         */
+    int32_t head_dim;          /* 64, 128 or 256                                              */
     int32_t block;             /* 128 (Appendix A: uniform block size)                        */
     float scale;               /* softmax scale tau; <= 0 selects 1/sqrt(head_dim)            */
     const int32_t *cu_seqlens_k; /* HOST, nseq+1 entries, or NULL (= cu_seqlens): key-side      */
@@ -94,7 +94,7 @@ const char *fp_status_string(fp_status s);
 fp_status fp_layout(const fp_shape *shape, int32_t *m_total, int32_t *n_max, int32_t *row_offset);
 
 /* Bytes of device memory a plan for `shape` needs (row tables + the pooled keys of Alg. 1 stage 1:
- * 2 x (key blocks) x Hkv x 128 bf16 plus two norms per pooled key); 0 if the shape is invalid or unsupported.  Host only. */
+ * 2 x (key blocks) x Hkv x head_dim bf16 plus two norms per pooled key); 0 if the shape is invalid or unsupported.  Host only. */
 size_t fp_workspace_bytes(const fp_shape *shape);
 
 /* Validates `shape`, selects `device`, allocates one device buffer of fp_workspace_bytes(shape)
@@ -134,7 +134,8 @@ fp_status fp_block_search(fp_plan *plan, const void *Q, const void *K, float eps
  * fp_block_search; the pooled keys of Alg. 1 stage 1 go to a fixed array inside the library
  * (FP_STATIC_SCRATCH_BYTES per GPU) instead of the plan's buffer, so `plan` may be one whose
  * workspace is in use elsewhere.  Limit: (key blocks of the batch) x Hkv x (2 planes x 256 B + 8 B
- * of norms) must fit, i.e. key blocks x Hkv <= 16384 (256K tokens at Hkv = 8, 512K at Hkv = 4); beyond it the call
+ * of norms) must fit, i.e. key blocks x Hkv <= 16384 at head_dim 128 (256K tokens at Hkv = 8, 512K at Hkv = 4; half as many
+ * at head_dim 256); beyond it the call
  * returns FP_ERR_STATIC_LIMIT and launches nothing.  The call allocates nothing and frees
  * nothing.  All calls on one GPU share that GPU's array: it needs no clearing (every entry a
  * call reads it has written first), but two calls that may overlap in time on one GPU (different

@@ -62,7 +62,7 @@ fp_status check_shape(const fp_shape *s, Layout *out) {
     for (int i = 0; i < s->nseq; ++i)
         if (s->cu_seqlens[i + 1] <= s->cu_seqlens[i] || cuk[i + 1] <= cuk[i]) return FP_ERR_INVALID_ARG;
     if (!(s->scale == s->scale) || std::isinf(s->scale)) return FP_ERR_INVALID_ARG;
-    if (s->head_dim != fp::kHeadDim || s->block != fp::kBlock) return FP_ERR_UNSUPPORTED;
+    if ((s->head_dim != 64 && s->head_dim != 128 && s->head_dim != 256) || s->block != fp::kBlock) return FP_ERR_UNSUPPORTED;
     Layout L;
     L.row_offset.assign((size_t)s->nseq + 1, 0);
     L.kb_offset.assign((size_t)s->nseq + 1, 0);
@@ -86,11 +86,33 @@ fp_status check_shape(const fp_shape *s, Layout *out) {
     return FP_OK;
 }
 
+int search_stage_bytes(int head_dim) {
+    return head_dim == 64 ? fp::kSearchStageBytes<64> : head_dim == 128 ? fp::kSearchStageBytes<128> : fp::kSearchStageBytes<256>;
+}
+int attn_lds_bytes(int head_dim) {
+    return head_dim == 64 ? fp::kAttnLds<64> : head_dim == 128 ? fp::kAttnLds<128> : fp::kAttnLds<256>;
+}
+
+template <int D>
+bool set_lds_ceilings() {
+    const int search_lds_max = fp::kSearchStageBytes<D> + fp::kSearchRowHeader + fp::kSearchHeads * kMaxBlocksPerSeq * (int)sizeof(float) + fp::kSearchCandBytes;
+    bool ok = hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<D, false>),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, search_lds_max) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<D, true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, search_lds_max) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<D, true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds<D>) == hipSuccess;
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<D, false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds<D>) == hipSuccess;
+    return ok;
+}
+
 }  // namespace
 
 struct fp_plan {
     int device = 0;
     int nseq = 0, hq = 0, hkv = 0, g = 0, T = 0;   // T: query tokens
+    int head_dim = 0;
     int m_total = 0, n_max = 0, kb_total = 0;
     float c = 0.f;                    // tau * log2(e)
     fp::RowRec *d_rows = nullptr;     // [m_total]
@@ -114,7 +136,7 @@ constexpr size_t kWsAlign = 256;
 struct WorkspaceMap {
     size_t rows = 0, rows_ranked = 0, order = 0, kblk = 0, kb_hi = 0, kb_lo = 0, kb_norm = 0, total = 0;
 };
-WorkspaceMap workspace_map(const Layout &L, int hkv) {
+WorkspaceMap workspace_map(const Layout &L, int hkv, int head_dim) {
     WorkspaceMap m;
     size_t off = 0;
     auto take = [&off](size_t bytes) {
@@ -122,7 +144,7 @@ WorkspaceMap workspace_map(const Layout &L, int hkv) {
         off += (bytes + kWsAlign - 1) / kWsAlign * kWsAlign;
         return at;
     };
-    const size_t kb_bytes = (size_t)L.kb_total * hkv * fp::kHeadDim * sizeof(uint16_t);
+    const size_t kb_bytes = (size_t)L.kb_total * hkv * head_dim * sizeof(uint16_t);
     m.rows = take((size_t)L.m_total * sizeof(fp::RowRec));
     m.rows_ranked = take((size_t)L.m_total * sizeof(fp::RowRec));
     m.order = take((size_t)L.m_total * sizeof(int32_t));
@@ -142,12 +164,12 @@ const char *fp_status_string(fp_status s) {
     switch (s) {
         case FP_OK: return "ok";
         case FP_ERR_INVALID_ARG: return "invalid argument";
-        case FP_ERR_UNSUPPORTED: return "unsupported shape (head_dim and block must be 128, at most 4096 blocks per sequence)";
+        case FP_ERR_UNSUPPORTED: return "unsupported shape (head_dim must be 64, 128 or 256, block 128, at most 4096 blocks per sequence, a KV prefix a multiple of the block)";
         case FP_ERR_DEVICE: return "HIP device error";
         case FP_ERR_NOMEM: return "out of host memory";
         case FP_ERR_STATIC_LIMIT:
             return "shape needs more pooled-key scratch than the library's built-in array holds (fp_block_search_static: "
-                   "key blocks x Hkv <= 16384); use fp_block_search";
+                   "key blocks x Hkv <= 16384 at head_dim 128); use fp_block_search";
         case FP_ERR_WORKSPACE: return "workspace too small or not 256-byte aligned (see fp_workspace_bytes)";
     }
     return "unknown status";
@@ -166,7 +188,7 @@ fp_status fp_layout(const fp_shape *shape, int32_t *m_total, int32_t *n_max, int
 size_t fp_workspace_bytes(const fp_shape *shape) {
     Layout L;
     if (check_shape(shape, &L) != FP_OK) return 0;
-    return workspace_map(L, shape->hkv).total;
+    return workspace_map(L, shape->hkv, shape->head_dim).total;
 }
 
 void fp_plan_destroy(fp_plan *p) {
@@ -190,7 +212,7 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
     Layout L;
     const fp_status st = check_shape(shape, &L);
     if (st != FP_OK) return st;
-    const WorkspaceMap wm = workspace_map(L, shape->hkv);
+    const WorkspaceMap wm = workspace_map(L, shape->hkv, shape->head_dim);
     if (workspace != nullptr && (workspace_bytes < wm.total || reinterpret_cast<uintptr_t>(workspace) % kWsAlign != 0))
         return FP_ERR_WORKSPACE;
     int ndev = 0;
@@ -203,6 +225,7 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
     p->hq = shape->hq;
     p->hkv = shape->hkv;
     p->g = shape->hq / shape->hkv;
+    p->head_dim = shape->head_dim;
     p->T = shape->cu_seqlens[shape->nseq];
     p->m_total = L.m_total;
     p->n_max = L.n_max;
@@ -210,7 +233,7 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
     const float tau = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
     p->c = tau * fp::kLog2e;
     p->n_pad = (L.n_max + 31) / 32 * 32;
-    p->search_lds = (size_t)fp::kSearchStageBytes + fp::kSearchRowHeader + (size_t)fp::kSearchHeads * p->n_pad * sizeof(float) + fp::kSearchCandBytes;
+    p->search_lds = (size_t)search_stage_bytes(shape->head_dim) + fp::kSearchRowHeader + (size_t)fp::kSearchHeads * p->n_pad * sizeof(float) + fp::kSearchCandBytes;
 
     const int32_t *cuk = shape->cu_seqlens_k ? shape->cu_seqlens_k : shape->cu_seqlens;
     std::vector<fp::RowRec> rows((size_t)L.m_total);
@@ -271,20 +294,12 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
     ok = ok && hipMemcpy(p->d_rows_ranked, rows_ranked.data(), rows.size() * sizeof(fp::RowRec), hipMemcpyHostToDevice) == hipSuccess;
     // The dynamic-LDS ceilings are per kernel, not per plan: they are set to what the largest
     // supported shape needs, so that plans of different sizes can be alive together.
-    const int search_lds_max = fp::kSearchStageBytes + fp::kSearchRowHeader + fp::kSearchHeads * kMaxBlocksPerSeq * (int)sizeof(float) + fp::kSearchCandBytes;
+    ok = ok && set_lds_ceilings<64>() && set_lds_ceilings<128>() && set_lds_ceilings<256>();
     const int thr_lds_max = fp::kThresholdWaves * kMaxBlocksPerSeq * (int)sizeof(float);
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, search_lds_max) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, search_lds_max) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel<true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, thr_lds_max) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel<false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, thr_lds_max) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds) == hipSuccess;
     (void)hipSetDevice(prev);
     if (!ok) {
         (void)hipGetLastError();
@@ -303,6 +318,28 @@ static bool on_plan_device(const fp_plan *p) {
     return hipGetDevice(&cur) == hipSuccess && cur == p->device;
 }
 
+extern "C++" {
+template <int D>
+static fp_status launch_search_d(fp_plan *p, const void *Q, const void *K, float eps, float *scores,
+                                 const fp::SelectArgs *sel, hipStream_t st, uint16_t *kb_hi, uint16_t *kb_lo,
+                                 float2 *kb_norm) {
+    fp::pool_k_kernel<D><<<dim3(p->kb_total, p->hkv), 256, 0, st>>>(static_cast<const uint16_t *>(K), p->d_kblk, p->hkv,
+                                                                     p->c, kb_hi, kb_lo, kb_norm);
+    const int nchunk = (p->g + fp::kSearchHeads - 1) / fp::kSearchHeads;
+    const dim3 grid(p->m_total * p->hkv * nchunk);
+    const uint16_t *q = static_cast<const uint16_t *>(Q);
+    if (sel != nullptr)
+        fp::search_kernel<D, true><<<grid, 256, p->search_lds, st>>>(q, kb_hi, kb_lo, kb_norm, p->d_rows_ranked, p->d_order,
+                                                                     p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
+                                                                     eps, nullptr, *sel);
+    else
+        fp::search_kernel<D, false><<<grid, 256, p->search_lds, st>>>(q, kb_hi, kb_lo, kb_norm, p->d_rows_ranked, p->d_order,
+                                                                      p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
+                                                                      eps, scores, fp::SelectArgs{});
+    return launch_status();
+}
+}  // extern "C++"
+
 // Alg. 1 stage 1 and stages 2-3; `sel` non-null selects the variant that applies Alg. 2 in place.
 static fp_status launch_search(fp_plan *p, const void *Q, const void *K, float eps, float *scores,
                                const fp::SelectArgs *sel, void *hip_stream, uint16_t *kb_hi = nullptr,
@@ -314,20 +351,11 @@ static fp_status launch_search(fp_plan *p, const void *Q, const void *K, float e
         kb_norm = p->d_kb_norm;
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    fp::pool_k_kernel<<<dim3(p->kb_total, p->hkv), 256, 0, st>>>(static_cast<const uint16_t *>(K), p->d_kblk, p->hkv,
-                                                                  p->c, kb_hi, kb_lo, kb_norm);
-    const int nchunk = (p->g + fp::kSearchHeads - 1) / fp::kSearchHeads;
-    const dim3 grid(p->m_total * p->hkv * nchunk);
-    const uint16_t *q = static_cast<const uint16_t *>(Q);
-    if (sel != nullptr)
-        fp::search_kernel<true><<<grid, 256, p->search_lds, st>>>(q, kb_hi, kb_lo, kb_norm, p->d_rows_ranked, p->d_order,
-                                                                  p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
-                                                                  eps, nullptr, *sel);
-    else
-        fp::search_kernel<false><<<grid, 256, p->search_lds, st>>>(q, kb_hi, kb_lo, kb_norm, p->d_rows_ranked, p->d_order,
-                                                                   p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
-                                                                   eps, scores, fp::SelectArgs{});
-    return launch_status();
+    switch (p->head_dim) {
+        case 64: return launch_search_d<64>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
+        case 128: return launch_search_d<128>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
+        default: return launch_search_d<256>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
+    }
 }
 
 static bool params_ok(const fp_params *params) {
@@ -341,7 +369,7 @@ fp_status fp_block_search(fp_plan *p, const void *Q, const void *K, float eps, f
 
 fp_status fp_block_search_static(fp_plan *p, const void *Q, const void *K, float eps, float *scores, void *hip_stream) {
     if (p == nullptr || Q == nullptr || K == nullptr || scores == nullptr || !(eps >= 0.f)) return FP_ERR_INVALID_ARG;
-    const size_t plane = ((size_t)p->kb_total * p->hkv * fp::kHeadDim * sizeof(uint16_t) + kWsAlign - 1) / kWsAlign * kWsAlign;
+    const size_t plane = ((size_t)p->kb_total * p->hkv * p->head_dim * sizeof(uint16_t) + kWsAlign - 1) / kWsAlign * kWsAlign;
     const size_t norms = (size_t)p->kb_total * p->hkv * sizeof(float2);
     if (2 * plane + norms > kStaticScratchBytes) return FP_ERR_STATIC_LIMIT;
     if (!on_plan_device(p)) return FP_ERR_DEVICE;
@@ -385,22 +413,34 @@ fp_status fp_threshold(fp_plan *p, const float *scores, const fp_params *params,
     return launch_status();
 }
 
-static fp_status launch_attn(fp_plan *p, bool sparse, const void *Q, const void *K, const void *V, const int32_t *idx,
-                             const int32_t *cnt, void *O, float *lse, void *hip_stream) {
-    if (!on_plan_device(p)) return FP_ERR_DEVICE;
+extern "C++" {
+template <int D>
+static fp_status launch_attn_d(fp_plan *p, bool sparse, const void *Q, const void *K, const void *V, const int32_t *idx,
+                               const int32_t *cnt, void *O, float *lse, hipStream_t st) {
     const int n_super = p->m_total * p->hkv;
     const int grid = (n_super + 7) / 8 * 8 * p->g;
-    hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const uint16_t *q = static_cast<const uint16_t *>(Q), *k = static_cast<const uint16_t *>(K),
                    *v = static_cast<const uint16_t *>(V);
     uint16_t *o = static_cast<uint16_t *>(O);
     if (sparse)
-        fp::attn_kernel<true><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, idx, cnt, p->d_rows_ranked, p->d_order, p->m_total, p->n_max,
-                                                           p->hq, p->hkv, p->g, p->T, p->c, o, lse);
+        fp::attn_kernel<D, true><<<dim3(grid), 256, fp::kAttnLds<D>, st>>>(q, k, v, idx, cnt, p->d_rows_ranked, p->d_order, p->m_total,
+                                                                          p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     else
-        fp::attn_kernel<false><<<dim3(grid), 256, fp::kAttnLds, st>>>(q, k, v, nullptr, nullptr, p->d_rows_ranked, p->d_order, p->m_total,
-                                                            p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
+        fp::attn_kernel<D, false><<<dim3(grid), 256, fp::kAttnLds<D>, st>>>(q, k, v, nullptr, nullptr, p->d_rows_ranked, p->d_order,
+                                                                           p->m_total, p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     return launch_status();
+}
+}  // extern "C++"
+
+static fp_status launch_attn(fp_plan *p, bool sparse, const void *Q, const void *K, const void *V, const int32_t *idx,
+                             const int32_t *cnt, void *O, float *lse, void *hip_stream) {
+    if (!on_plan_device(p)) return FP_ERR_DEVICE;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    switch (p->head_dim) {
+        case 64: return launch_attn_d<64>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
+        case 128: return launch_attn_d<128>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
+        default: return launch_attn_d<256>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
+    }
 }
 
 fp_status fp_sparse_prefill(fp_plan *p, const void *Q, const void *K, const void *V, const int32_t *idx,

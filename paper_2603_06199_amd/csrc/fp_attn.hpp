@@ -5,19 +5,23 @@
 
 namespace fp {
 
-// LDS: three K buffers and two V buffers of one 64-key tile (64 rows x 256 B, unpadded) each.
+// LDS: three K buffers and two V buffers of one 64-key tile (64 rows x 2D bytes, unpadded) each.
 // Tiles are written by direct global->LDS loads (16 B per lane, lane i lands at base + 16 i), so
-// bank conflicts are avoided by permuting the 16-byte chunks inside a row instead of padding:
+// bank conflicts are avoided by permuting the 16-byte chunks inside a row instead of padding
+// (stated for head dimension 128, 16 chunks per row; the masks shrink with the row for 64):
 //   K row r keeps chunk c at position c ^ (r & 15): the A-fragment reads of 16 consecutive rows
 //     at one chunk index then hit 16 different bank groups;
 //   V row r keeps chunk c at position c ^ 4 (r & 3): the four rows a transpose read touches per
 //     lane group then hit four different 64-byte bank groups.
+// Head dimension 128: 16 KB tiles, 80 KB, two workgroups per CU.  64: 40 KB.  256: 32 KB tiles,
+// all 160 KB of a CU, one workgroup (its accumulators and query fragments need 512 registers).
 constexpr int kAttnTileKeys = 64;
-constexpr int kAttnRowBytes = 256;
-constexpr int kAttnTile = kAttnTileKeys * kAttnRowBytes;   // 16384
+template <int D> constexpr int kAttnRowBytes = 2 * D;
+template <int D> constexpr int kAttnTile = kAttnTileKeys * kAttnRowBytes<D>;   // 16384 at D = 128
 constexpr int kAttnKBufs = 3, kAttnVBufs = 2;
-constexpr int kAttnVBase = kAttnKBufs * kAttnTile;
-constexpr int kAttnLds = (kAttnKBufs + kAttnVBufs) * kAttnTile;   // 81920: two workgroups per CU
+template <int D> constexpr int kAttnVBase = kAttnKBufs * kAttnTile<D>;
+template <int D> constexpr int kAttnLds = (kAttnKBufs + kAttnVBufs) * kAttnTile<D>;   // 81920 at D = 128
+template <int D> constexpr int kAttnVSwz = (D / 32 - 1 < 3 ? D / 32 - 1 : 3);     // V rows: chunk ^ 4 (r & kAttnVSwz)
 
 // ds_read_b64_tr_b16: within each group of 16 lanes the 16 x 4 b16 values addressed by the
 // lanes (lane j supplies 4 consecutive b16) are exchanged so that lane i receives, in element e,
@@ -67,14 +71,15 @@ __device__ __forceinline__ int attn_tile_block(const int32_t *list, int t, int I
 
 // S^T (64 keys x 32 queries) of one K tile: s0 = keys 0..31, s1 = keys 32..63.
 // kaddr = buffer base + the lane's row and swizzled chunk for k-slice 0; slice ks sits at kaddr ^ (ks << 5).
-__device__ __forceinline__ void attn_qk(const char *smem, uint32_t kaddr, const bf16x8 (&qb)[8], f32x16 &s0, f32x16 &s1) {
+template <int D>
+__device__ __forceinline__ void attn_qk(const char *smem, uint32_t kaddr, const bf16x8 (&qb)[D / 16], f32x16 &s0, f32x16 &s1) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < D / 16; ++ks) {
         const char *kp = smem + (kaddr ^ (uint32_t)(ks << 5));
         const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(kp);
-        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(kp + 32 * kAttnRowBytes);
+        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(kp + 32 * kAttnRowBytes<D>);
         s0 = mfma32(a0, qb[ks], s0);
         s1 = mfma32(a1, qb[ks], s1);
     }
@@ -111,64 +116,69 @@ __device__ __forceinline__ float attn_rowmax(const f32x16 &s0, const f32x16 &s1)
 // depend on the reference point.  With 32 rows per wave an exact-max rule would fire on most
 // tiles of a short row; this one fires a few times per row at most.
 constexpr float kAttnLazy = 8.0f;
-__device__ __forceinline__ void attn_new_max(float tm, float c, float &m_run, float &l_run, f32x16 (&acc)[4]) {
+template <int NDT>
+__device__ __forceinline__ void attn_new_max(float tm, float c, float &m_run, float &l_run, f32x16 (&acc)[NDT]) {
     const float m_new = fmaxf(m_run, tm);
     if (__ballot((m_new - m_run) * c > kAttnLazy)) {
         const float a = fast_exp2((m_run - m_new) * c);
         l_run *= a;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[dt][i] *= a;
         m_run = m_new;
     }
 }
 
-// p = 2^(c*s - c*m) rounded to bf16, laid out as the B operand of the PV product; the row sum is
-// taken over the rounded values (the ones that multiply V), two per VALU op.
+// p = 2^(c*s - c*m), rounded to bf16 and laid out as the B operand of the PV product; the row sum
+// is taken over the fp32 values before rounding, so lse does not inherit bf16's 2^-9 rounding.
 __device__ __forceinline__ void attn_exp(const f32x16 &s0, const f32x16 &s1, float c, float mc, float &l_run,
                                          bf16x8 (&pb)[2][2]) {
+    float la = 0.f, lb = 0.f;
 #pragma unroll
-    for (int i = 0; i < 16; i += 2) {
-        bf16x2 a, b;
-        a[0] = (__bf16)fast_exp2(__builtin_fmaf(s0[i], c, -mc));
-        a[1] = (__bf16)fast_exp2(__builtin_fmaf(s0[i + 1], c, -mc));
-        b[0] = (__bf16)fast_exp2(__builtin_fmaf(s1[i], c, -mc));
-        b[1] = (__bf16)fast_exp2(__builtin_fmaf(s1[i + 1], c, -mc));
-        l_run = add_pair(a, l_run);
-        l_run = add_pair(b, l_run);
-        pb[0][i >> 3][i & 7] = a[0];
-        pb[0][i >> 3][(i & 7) + 1] = a[1];
-        pb[1][i >> 3][i & 7] = b[0];
-        pb[1][i >> 3][(i & 7) + 1] = b[1];
+    for (int i = 0; i < 16; ++i) {
+        const float pa = fast_exp2(__builtin_fmaf(s0[i], c, -mc));
+        const float pq = fast_exp2(__builtin_fmaf(s1[i], c, -mc));
+        la += pa;
+        lb += pq;
+        pb[0][i >> 3][i & 7] = (__bf16)pa;
+        pb[1][i >> 3][i & 7] = (__bf16)pq;
     }
+    l_run += la + lb;
 }
 
 // O^T += V^T P^T for one 64-key tile: V^T fragments by transpose reads of the row-major V tile.
 // vaddr[dt] = buffer base + the lane's row/column offsets with the swizzle of d-tile dt folded in.
-__device__ __forceinline__ void attn_pv(const char *smem, const uint32_t (&vaddr)[4], const bf16x8 (&pb)[2][2],
-                                        f32x16 (&acc)[4]) {
+template <int D>
+__device__ __forceinline__ void attn_pv(const char *smem, const uint32_t (&vaddr)[D / 32], const bf16x8 (&pb)[2][2],
+                                        f32x16 (&acc)[D / 32]) {
 #pragma unroll
     for (int kt2 = 0; kt2 < 2; ++kt2)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int dt = 0; dt < 4; ++dt) {
-                const char *vp = smem + vaddr[dt] + (32 * kt2 + 16 * j) * kAttnRowBytes;
+            for (int dt = 0; dt < D / 32; ++dt) {
+                const char *vp = smem + vaddr[dt] + (32 * kt2 + 16 * j) * kAttnRowBytes<D>;
                 const s16x4 lo = lds_read_tr(vp);
-                const s16x4 hi = lds_read_tr(vp + 8 * kAttnRowBytes);
+                const s16x4 hi = lds_read_tr(vp + 8 * kAttnRowBytes<D>);
                 const s16x8 a = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 acc[dt] = mfma32(__builtin_bit_cast(bf16x8, a), pb[kt2][j], acc[dt]);
             }
 }
 
-template <bool SPARSE>
-__global__ __launch_bounds__(256, 2) void attn_kernel(
+template <int D, bool SPARSE>
+__global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ cnt, const RowRec *__restrict__ rows_ranked,
     const int32_t *__restrict__ order, int m_total, int n_max, int hq, int hkv, int g, int T, float c,
     uint16_t *__restrict__ O, float *__restrict__ lse) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
+    constexpr int KS = D / 16;            // k-slices of the QK^T contraction
+    constexpr int NDT = D / 32;           // 32-wide tiles of the head dimension in the output
+    constexpr int LPT = D / 32;           // wave-wide 1 KB loads per wave and tile (64 rows over 4 waves)
+    constexpr int RPL = kRowsPerLoad<D>;  // rows one such load covers
+    constexpr int LPR = kChunks<D>;       // lanes (= 16-byte chunks) per row
+    constexpr int RB = kAttnRowBytes<D>;
 
     const int x = blockIdx.x & 7, k = blockIdx.x >> 3;
     const int s = (k / g) * 8 + x, hg = k % g;
@@ -204,10 +214,10 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
 
     if (ntiles == 0) {   // empty list: O = 0, lse = -inf (uniform exit, before any barrier)
         if (q_local < bi.q_len) {
-            uint16_t *op = O + ((size_t)(bi.q_tok0 + q_local) * hq + h) * kHeadDim + 64 * half;
+            uint16_t *op = O + ((size_t)(bi.q_tok0 + q_local) * hq + h) * D + (D / 2) * half;
             const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
-            for (int i = 0; i < 8; ++i) *reinterpret_cast<u32x4 *>(op + 8 * i) = z;
+            for (int i = 0; i < D / 16; ++i) *reinterpret_cast<u32x4 *>(op + 8 * i) = z;
             if (lse != nullptr && half == 0) lse[(size_t)h * T + bi.q_tok0 + q_local] = -INFINITY;
         }
         return;
@@ -219,53 +229,54 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     // assembly so that their completion is counted here and not by the compiler, which cannot see
     // the tile loads queued behind them and would wait for those too: the prologue waits once,
     // with the exact count, for the fragments and the first K tile together.
-    bf16x8 qb[8];
+    bf16x8 qb[KS];
     {
         int row = q_local < bi.q_len ? q_local : bi.q_len - 1;
-        const uint16_t *qp = Q + ((size_t)(bi.q_tok0 + row) * hq + h) * kHeadDim + 8 * half;
+        const uint16_t *qp = Q + ((size_t)(bi.q_tok0 + row) * hq + h) * D + 8 * half;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+        for (int ks = 0; ks < KS; ++ks)
             asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=&v"(qb[ks]) : "v"(qp), "n"(32 * ks) : "memory");
     }
 
-    // Tile loads.  One wave-wide instruction moves 4 rows (1 KB); wave w loads rows 16w + 4i + l/16
-    // (i = 0..3) of a K or V tile.  Lane l fills LDS position l%16 of its row, i.e. it fetches the
-    // global chunk (l%16) ^ swizzle(row).  The global address is a wave-uniform base (first token
+    // Tile loads.  One wave-wide instruction moves RPL = 512/D rows (1 KB); wave w loads rows
+    // 16w + RPL i + l/LPR (i < LPT) of a K or V tile (head dimension 128: 4 rows per instruction,
+    // rows 16w + 4i + l/16).  Lane l fills LDS position l % LPR of its row, i.e. it fetches the
+    // global chunk (l % LPR) ^ swizzle(row).  The global address is a wave-uniform base (first token
     // of the tile, KV head) plus a per-lane 32-bit byte offset.  Only a tile that reaches past
     // the end of its sequence (ragged last block) needs per-row clamping; its base is clamped
     // too, so the unsigned row offsets can never wrap.
-    const uint32_t row_bytes = (uint32_t)hkv * kHeadDim * 2;
+    const uint32_t row_bytes = (uint32_t)hkv * D * 2;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(FP_LDS(char) *)smem;
-    const int ld_row = 16 * w + (l >> 4);   // + 4i
-    const int ld_pos = l & 15;
-    const char *Kb = reinterpret_cast<const char *>(K) + (size_t)hk * kHeadDim * 2;
-    const char *Vb = reinterpret_cast<const char *>(V) + (size_t)hk * kHeadDim * 2;
-    uint32_t ld_kcol[4], ld_vcol[4];
+    const int ld_row = 16 * w + l / LPR;   // + RPL i
+    const int ld_pos = l % LPR;
+    const char *Kb = reinterpret_cast<const char *>(K) + (size_t)hk * D * 2;
+    const char *Vb = reinterpret_cast<const char *>(V) + (size_t)hk * D * 2;
+    uint32_t ld_kcol[LPT], ld_vcol[LPT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const int row = ld_row + 4 * i;
-        ld_kcol[i] = (uint32_t)((ld_pos ^ (row & 15)) * 16);
-        ld_vcol[i] = (uint32_t)((ld_pos ^ (4 * (row & 3))) * 16);
+    for (int i = 0; i < LPT; ++i) {
+        const int row = ld_row + RPL * i;
+        ld_kcol[i] = (uint32_t)((ld_pos ^ (row & kSwz<D>)) * 16);
+        ld_vcol[i] = (uint32_t)((ld_pos ^ (4 * (row & kAttnVSwz<D>))) * 16);
     }
 #define FP_LOAD(FULL, Xb, col_, blk_, odd_, ldsoff_)                                                      \
     do {                                                                                                  \
         const int tok0_ = seq_tok0 + (blk_) * kBlock + (odd_) * kAttnTileKeys;                            \
         const int base_tok_ = tok0_ < last_tok ? tok0_ : last_tok;                                        \
         const char *base_ = Xb + (size_t)base_tok_ * row_bytes;                                           \
-        const uint32_t dst_ = lds_base + (ldsoff_) + 16 * w * kAttnRowBytes;                              \
-        _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                                \
-            uint32_t ro_ = (uint32_t)(ld_row + 4 * i_) * row_bytes;                                       \
+        const uint32_t dst_ = lds_base + (ldsoff_) + 16 * w * RB;                                         \
+        _Pragma("unroll") for (int i_ = 0; i_ < LPT; ++i_) {                                              \
+            uint32_t ro_ = (uint32_t)(ld_row + RPL * i_) * row_bytes;                                     \
             if (!(FULL)) {                                                                                \
-                int tok_ = tok0_ + ld_row + 4 * i_;                                                       \
+                int tok_ = tok0_ + ld_row + RPL * i_;                                                     \
                 tok_ = tok_ < last_tok ? tok_ : last_tok; /* keys past the end are masked as future */    \
                 ro_ = (uint32_t)(tok_ - base_tok_) * row_bytes; /* tok_ >= base_tok_ */                   \
             }                                                                                             \
-            load_to_lds(base_, ro_ + col_[i_], dst_ + 4 * i_ * kAttnRowBytes);                            \
+            load_to_lds(base_, ro_ + col_[i_], dst_ + i_ * 1024);                                         \
         }                                                                                                 \
     } while (0)
     // K tile t lives in K buffer t % 3, V tile t in V buffer t % 2.
-#define FP_KBUF(t) ((uint32_t)(((t) % kAttnKBufs) * kAttnTile))
-#define FP_VBUF(t) ((uint32_t)(kAttnVBase + ((t) & 1) * kAttnTile))
+#define FP_KBUF(t) ((uint32_t)(((t) % kAttnKBufs) * kAttnTile<D>))
+#define FP_VBUF(t) ((uint32_t)(kAttnVBase<D> + ((t) & 1) * kAttnTile<D>))
     // FULL loads are for tiles known to lie before the diagonal block, hence complete; the block id
     // is kept below I so that even a malformed (non-ascending) list cannot reach past the sequence.
     // Other loads clamp every row to the sequence's last token, and the tile index to the row's
@@ -281,26 +292,27 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
         FP_LOAD(false, Xb, col_, FP_TILE_BLOCK(ts_), (ts_ & 1), ldsoff_);                                 \
     } while (0)
 
-    f32x16 acc[4];
+    f32x16 acc[NDT];
 #pragma unroll
-    for (int dt = 0; dt < 4; ++dt)
+    for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[dt][i] = 0.f;
     float m_run = -INFINITY;   // reference point of the exponentials (raw dot-product units), see attn_new_max
     float l_run = 0.f;         // this lane's share of the running row sum
 
-    // Fragment addresses inside a buffer.  K: rows l%32 and 32 + l%32, chunk (2ks + half) ^ (row & 15).
+    // Fragment addresses inside a buffer.  K: rows l%32 and 32 + l%32, chunk
+    // (2ks + half) ^ (row & kSwz) = 2ks ^ (half ^ (row & kSwz)); rows 32 apart share the permutation.
     const int krow = l & 31;
-    const uint32_t k_frag =
-        (uint32_t)(krow * kAttnRowBytes + ((((krow >> 1) & 7) << 5) | ((half ^ (krow & 1)) << 4)));
+    const uint32_t k_frag = (uint32_t)(krow * RB + ((half ^ (krow & kSwz<D>)) << 4));
     // V transpose reads: row 32kt + 16j + 4half + e (+8), e = (l%16)/4 = row & 3; 8-byte unit at
-    // dims 32dt + 16gq + 4cc, i.e. chunk 4dt + 2gq + cc/2, stored at chunk ^ 4e = 4(dt ^ e) + ...
-    uint32_t v_frag[4];
+    // dims 32dt + 16gq + 4cc, i.e. chunk 4dt + 2gq + cc/2, stored at chunk ^ 4(e & kAttnVSwz)
+    // = 4(dt ^ (e & kAttnVSwz)) + ...
+    uint32_t v_frag[NDT];
     {
         const int e = (l & 15) >> 2, gq = (l & 31) >> 4, cc = l & 3;
-        const uint32_t vb = (uint32_t)((4 * half + e) * kAttnRowBytes + (2 * gq + (cc >> 1)) * 16 + 8 * (cc & 1));
+        const uint32_t vb = (uint32_t)((4 * half + e) * RB + (2 * gq + (cc >> 1)) * 16 + 8 * (cc & 1));
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt) v_frag[dt] = vb + (uint32_t)((dt ^ e) * 64);
+        for (int dt = 0; dt < NDT; ++dt) v_frag[dt] = vb + (uint32_t)((dt ^ (e & kAttnVSwz<D>)) * 64);
     }
     // Causal limit of tile t for this lane: on the diagonal block, key kk of the tile is in the
     // lane's future if kk > query - tile offset (and keys past a ragged end lie beyond every stored
@@ -312,15 +324,15 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
     FP_LOAD(false, Vb, ld_vcol, b0, 0, FP_VBUF(0));
     FP_LOAD(false, Kb, ld_kcol, b0, 1, FP_KBUF(1));   // ntiles >= 2
     FP_LOAD(false, Kb, ld_kcol, (nb > 1 ? b1 : b0), (nb > 1 ? 0 : 1), FP_KBUF(2));
-    FP_WAIT_VMCNT(12);   // Q and K[0] are in; V[0] and K[1] keep landing under the first QK^T
+    FP_WAIT_VMCNT(3 * LPT);   // Q and K[0] are in; V[0], K[1] and K[2] keep landing under the first QK^T
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qb[ks]));   // uses of Q stay behind the wait
+    for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qb[ks]));   // uses of Q stay behind the wait
     __syncthreads();
     f32x16 sA0, sA1, sB0, sB1;
-    attn_qk(smem, FP_KBUF(0) + k_frag, qb, sA0, sA1);
+    attn_qk<D>(smem, FP_KBUF(0) + k_frag, qb, sA0, sA1);
     attn_mask(sA0, sA1, b0 == I ? q_local - 4 * half : 2 * kAttnTileKeys);
     m_run = attn_rowmax(sA0, sA1);   // finite: key 0 of tile 0 is visible to every query
-    FP_WAIT_VMCNT(4);
+    FP_WAIT_VMCNT(LPT);
     __syncthreads();
 
     // Step t.  On entry K[t+1] and V[t] are complete in LDS, K[t+2] may still be landing, S^T(t) is
@@ -349,17 +361,17 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
         }                                                                                                 \
         bf16x8 pb_[2][2];                                                                                 \
         attn_exp(c0, c1, c, m_run * c, l_run, pb_);                                                       \
-        if (MODE != LAST) attn_qk(smem, FP_KBUF(t_ + 1) + k_frag, qb, n0, n1);                            \
+        if (MODE != LAST) attn_qk<D>(smem, FP_KBUF(t_ + 1) + k_frag, qb, n0, n1);                         \
         {                                                                                                 \
-            uint32_t va_[4];                                                                              \
-            _Pragma("unroll") for (int dt_ = 0; dt_ < 4; ++dt_) va_[dt_] = FP_VBUF(t_) + v_frag[dt_];     \
-            attn_pv(smem, va_, pb_, acc);                                                                 \
+            uint32_t va_[NDT];                                                                            \
+            _Pragma("unroll") for (int dt_ = 0; dt_ < NDT; ++dt_) va_[dt_] = FP_VBUF(t_) + v_frag[dt_];   \
+            attn_pv<D>(smem, va_, pb_, acc);                                                              \
         }                                                                                                 \
         if (MODE != LAST) {                                                                               \
             if (MODE != MAIN) attn_mask(n0, n1, FP_LIM(t_ + 1));                                          \
-            attn_new_max(attn_rowmax(n0, n1), c, m_run, l_run, acc);                                      \
+            attn_new_max<NDT>(attn_rowmax(n0, n1), c, m_run, l_run, acc);                                 \
             if (MODE == PEN) FP_WAIT_VMCNT(0);                                                            \
-            else FP_WAIT_VMCNT(4);                                                                        \
+            else FP_WAIT_VMCNT(LPT);                                                                      \
             __syncthreads();                                                                              \
         }                                                                                                 \
     } while (0)
@@ -384,34 +396,34 @@ __global__ __launch_bounds__(256, 2) void attn_kernel(
 
     // O = acc / l, lse = m + log2 l (Alg. 3, final normalisation); rows past a ragged end are not stored.
     // Each lane holds 4 consecutive dims of one query per accumulator group, which would make every
-    // global store touch 64 different rows.  The wave's 32 x 128 output tile is therefore turned
-    // through LDS (its own 8 KB of the K buffers: their last reader and their last incoming load
-    // finished before the barrier of the last-but-one step) into 16-byte pieces, 16 lanes per row.
-    // Chunk c of row q is kept at chunk c ^ (q & 15) so that neither side meets a bank conflict.
+    // global store touch 64 different rows.  The wave's 32 x D output tile is therefore turned
+    // through LDS (its own 32 rows of the K buffers: their last reader and their last incoming load
+    // finished before the barrier of the last-but-one step) into 16-byte pieces, D/8 lanes per row.
+    // Chunk c of row q is kept at chunk c ^ (q & kSwz) so that neither side meets a bank conflict.
     const float l_tot = halves_sum(l_run);
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     {
-        char *ob = smem + w * (32 * kAttnRowBytes);
+        char *ob = smem + w * (32 * RB);
         const int qrow = l & 31;
 #pragma unroll
-        for (int dt = 0; dt < 4; ++dt)
+        for (int dt = 0; dt < NDT; ++dt)
 #pragma unroll
             for (int q4 = 0; q4 < 4; ++q4) {
                 bf16x4 o;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) o[e] = (__bf16)(acc[dt][4 * q4 + e] * inv);
-                *reinterpret_cast<bf16x4 *>(ob + qrow * kAttnRowBytes + (((4 * dt + q4) ^ (qrow & 15)) << 4) + 8 * half) = o;
+                *reinterpret_cast<bf16x4 *>(ob + qrow * RB + (((4 * dt + q4) ^ (qrow & kSwz<D>)) << 4) + 8 * half) = o;
             }
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        const int pc = l & 15;
+        const int pc = l % LPR;
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int orow = 4 * i + (l >> 4);
-            const u32x4 v = *reinterpret_cast<const u32x4 *>(ob + orow * kAttnRowBytes + (pc << 4));
+        for (int i = 0; i < 32 / RPL; ++i) {
+            const int orow = RPL * i + l / LPR;
+            const u32x4 v = *reinterpret_cast<const u32x4 *>(ob + orow * RB + (pc << 4));
             if (32 * w + orow < bi.q_len)
-                *reinterpret_cast<u32x4 *>(O + ((size_t)(bi.q_tok0 + 32 * w + orow) * hq + h) * kHeadDim + ((pc ^ (orow & 15)) << 3)) = v;
+                *reinterpret_cast<u32x4 *>(O + ((size_t)(bi.q_tok0 + 32 * w + orow) * hq + h) * D + ((pc ^ (orow & kSwz<D>)) << 3)) = v;
         }
     }
     if (q_local < bi.q_len && lse != nullptr && half == 0)

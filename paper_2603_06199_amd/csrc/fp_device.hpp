@@ -15,7 +15,12 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
 constexpr int kBlock = 128;    // tokens per block (Appendix A)
-constexpr int kHeadDim = 128;
+// The kernels are templates over the head dimension D (64, 128 or 256).  A row of D bf16 is
+// D/8 16-byte chunks; LDS tiles are unpadded and keep chunk c of row r at position c ^ (r & kSwz<D>)
+// (see the kernels), where the mask is the row's chunk count minus one, capped at 15.
+template <int D> constexpr int kChunks = D / 8;                            // 16-byte chunks per row
+template <int D> constexpr int kSwz = (D / 8 < 16 ? D / 8 : 16) - 1;       // chunk permutation mask
+template <int D> constexpr int kRowsPerLoad = 512 / D;                     // rows one 1 KB wave-wide load covers
 constexpr float kLog2e = 1.4426950408889634f;
 
 // One q-block row.  Queries: first token of the block (index into Q and O) and the number of
@@ -85,12 +90,6 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // VALU read of its result are inserted by the compiler, and inline assembly would not get them.
 __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(fmaxf(a, b), c); }
 
-// acc + lo(p) + hi(p) for a packed pair of bf16, one VALU op (v_dot2c_f32_bf16).
-__device__ __forceinline__ float add_pair(bf16x2 p, float acc) {
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    return __builtin_amdgcn_fdot2_f32_bf16(p, ones, acc, false);
-}
-
 // 16 bytes per lane, global -> LDS, no register staging: lane i's 16 bytes, fetched from
 // sbase + voff, land at LDS byte address lds_addr + 16 i (lds_addr is wave-uniform and goes to
 // M0).  Written as inline assembly on purpose: the compiler then neither tracks these loads in
@@ -104,7 +103,8 @@ __device__ __forceinline__ void load_to_lds(const char *sbase, uint32_t voff, ui
                  : "memory");
 }
 
-// s_waitcnt vmcnt(n) alone (expcnt and lgkmcnt left at "no wait"), n < 16
-#define FP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | (n))
+// s_waitcnt vmcnt(n) alone (expcnt and lgkmcnt left at "no wait"), n < 64: the count's low four
+// bits sit in bits 3:0 of the immediate, its high two in bits 15:14
+#define FP_WAIT_VMCNT(n) __builtin_amdgcn_s_waitcnt(0x0f70 | ((n) & 15) | (((n) >> 4) << 14))
 
 }  // namespace fp

@@ -6,29 +6,32 @@
 namespace fp {
 
 // ---------------------------------------------------------------------------------------------
-// Alg. 1 stage 1.  One workgroup per (key block, KV head): 128 keys x 128 dims are read once,
-// coalesced (16 lanes cover one 256-byte key row), summed in fp32 and reduced through LDS.
+// Alg. 1 stage 1.  One workgroup per (key block, KV head): 128 keys x D dims are read once,
+// coalesced (D/8 lanes cover one key row), summed in fp32 and reduced through LDS.
 // The mean is multiplied by c = tau*log2(e) here, once per pooled key, so that the score kernel's
 // products come out as base-2 logits, and stored as two bf16 planes, hi = bf16(c*mean) and
 // lo = bf16(c*mean - hi): fed to bf16 MFMA twice they keep ~16 mantissa bits of the pooled key.
 // Next to the planes go two norms per pooled key: |hi + lo|_2 (bounds every logit against it by
 // Cauchy-Schwarz) and |lo|_2 (bounds what a product with the hi plane alone leaves out).
 // ---------------------------------------------------------------------------------------------
+template <int D>
 __global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict__ K,
                                                      const KeyBlockRec *__restrict__ kblk, int hkv, float c,
                                                      uint16_t *__restrict__ kb_hi, uint16_t *__restrict__ kb_lo,
                                                      float2 *__restrict__ kb_norm) {
-    __shared__ float red[16][kHeadDim + 4];
-    __shared__ float2 nrm[2];
+    constexpr int CPR = kChunks<D>;   // lanes per key row
+    constexpr int RG = 256 / CPR;     // key rows per pass
+    __shared__ float red[RG][D + 4];
+    __shared__ float2 nrm[4];
     const int r = blockIdx.x, hk = blockIdx.y;
     const KeyBlockRec bi = kblk[r];
-    const int t = threadIdx.x, chunk = t & 15, rg = t >> 4;
+    const int t = threadIdx.x, chunk = t % CPR, rg = t / CPR;
     float acc[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) acc[j] = 0.f;
     const uint4 *base = reinterpret_cast<const uint4 *>(K);
-    for (int k = rg; k < bi.y; k += 16) {
-        const uint4 v = base[((size_t)(bi.x + k) * hkv + hk) * 16 + chunk];
+    for (int k = rg; k < bi.y; k += RG) {
+        const uint4 v = base[((size_t)(bi.x + k) * hkv + hk) * CPR + chunk];
         acc[0] += bf16lo(v.x); acc[1] += bf16hi(v.x);
         acc[2] += bf16lo(v.y); acc[3] += bf16hi(v.y);
         acc[4] += bf16lo(v.z); acc[5] += bf16hi(v.z);
@@ -37,14 +40,14 @@ __global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict_
 #pragma unroll
     for (int j = 0; j < 8; ++j) red[rg][chunk * 8 + j] = acc[j];
     __syncthreads();
-    if (t < kHeadDim) {
+    if (t < D) {   // whole waves: D is a multiple of 64
         float s = 0.f;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) s += red[i][t];
+        for (int i = 0; i < RG; ++i) s += red[i][t];
         const float v = (s / (float)bi.y) * c;
         const __bf16 hi = (__bf16)v;
         const __bf16 lo = (__bf16)(v - (float)hi);
-        const size_t o = ((size_t)r * hkv + hk) * kHeadDim + t;
+        const size_t o = ((size_t)r * hkv + hk) * D + t;
         kb_hi[o] = __builtin_bit_cast(uint16_t, hi);
         kb_lo[o] = __builtin_bit_cast(uint16_t, lo);
         const float both = (float)hi + (float)lo;
@@ -52,7 +55,15 @@ __global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict_
         if ((t & 63) == 0) nrm[t >> 6] = make_float2(n2, l2);
     }
     __syncthreads();
-    if (t == 0) kb_norm[(size_t)r * hkv + hk] = make_float2(sqrtf(nrm[0].x + nrm[1].x), sqrtf(nrm[0].y + nrm[1].y));
+    if (t == 0) {
+        float n2 = 0.f, l2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < D / 64; ++i) {
+            n2 += nrm[i].x;
+            l2 += nrm[i].y;
+        }
+        kb_norm[(size_t)r * hkv + hk] = make_float2(sqrtf(n2), sqrtf(l2));
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -84,12 +95,12 @@ __global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict_
 // interval [t_J - eps_J, t_J + eps_J] straddles the threshold.  Every other pair is decided with
 // a margin, so the lists are those of exact scores.
 // ---------------------------------------------------------------------------------------------
-constexpr int kSearchPlane = 32 * 256;                 // one plane (hi or lo) of a 32-row tile, unpadded
-constexpr int kSearchTile = 2 * kSearchPlane;          // hi + lo
+template <int D> constexpr int kSearchPlane = 32 * 2 * D;           // one plane (hi or lo) of a 32-row tile, unpadded
+template <int D> constexpr int kSearchTile = 2 * kSearchPlane<D>;   // hi + lo
 constexpr int kSearchBufs = 2;
 constexpr int kSearchHeads = 2;                        // query heads per workgroup
 constexpr int kSearchMailbox = 2 * kSearchHeads * 32 * 8;   // [step parity][head][pooled key] (max, sum)
-constexpr int kSearchStageBytes = kSearchBufs * kSearchTile + kSearchMailbox;
+template <int D> constexpr int kSearchStageBytes = kSearchBufs * kSearchTile<D> + kSearchMailbox;
 constexpr int kSearchRowHeader = 64;                   // per-head row maxima and prologue exchange, ahead of the rows
 constexpr int kSearchCandBytes = kSearchHeads * (32 + 4) * 4;   // SELECT: candidate tile indices + count per head
 constexpr float kSearchSafeLogit = 100.f;              // |x| below this: 2^x needs no reference point in fp32
@@ -97,21 +108,22 @@ constexpr float kSearchEpsNoop = 0x1p-26f;             // eps below this cannot 
 constexpr int kSearchExactTiles = 8;                   // SELECT: rows of up to this many tiles run both planes throughout
 
 // 64 x 32 logits of one pooled-key tile: acc[qt] = Q[qt] (hi + lo)^T, or Q[qt] hi^T.  baddr =
-// buffer base + the lane's row and swizzled chunk for k-slice 0 (slice ks sits at baddr ^ (ks << 5)).
-template <bool BOTH>
-__device__ __forceinline__ void search_mma(const char *smem, uint32_t baddr, const bf16x8 (&qa)[2][8], f32x16 (&acc)[2]) {
+// buffer base + the lane's row and swizzled chunk for k-slice 0; slice ks (dims 16ks..16ks+15, chunks
+// 2ks and 2ks+1) sits at baddr ^ (ks << 5) because the chunk permutation is an XOR.
+template <int D, bool BOTH>
+__device__ __forceinline__ void search_mma(const char *smem, uint32_t baddr, const bf16x8 (&qa)[2][D / 16], f32x16 (&acc)[2]) {
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[qt][i] = 0.f;
 #pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
+    for (int ks = 0; ks < D / 16; ++ks) {
         const char *bp = smem + (baddr ^ (uint32_t)(ks << 5));
         const bf16x8 bh = *reinterpret_cast<const bf16x8 *>(bp);
         acc[0] = mfma32(qa[0][ks], bh, acc[0]);
         acc[1] = mfma32(qa[1][ks], bh, acc[1]);
         if (BOTH) {
-            const bf16x8 bl = *reinterpret_cast<const bf16x8 *>(bp + kSearchPlane);
+            const bf16x8 bl = *reinterpret_cast<const bf16x8 *>(bp + kSearchPlane<D>);
             acc[0] = mfma32(qa[0][ks], bl, acc[0]);
             acc[1] = mfma32(qa[1][ks], bl, acc[1]);
         }
@@ -174,13 +186,14 @@ __device__ __forceinline__ float2 search_merge(float2 a, float2 b) {
 
 // Largest squared norm among this wave's 64 query rows: each lane holds half of the dims of two
 // rows (the other half is in lane l^32), two bf16 per v_dot2.
-__device__ __forceinline__ float search_qnorm2(const bf16x8 (&qa)[2][8]) {
+template <int D>
+__device__ __forceinline__ float search_qnorm2(const bf16x8 (&qa)[2][D / 16]) {
     float n2[2];
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         float a = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks)
+        for (int ks = 0; ks < D / 16; ++ks)
 #pragma unroll
             for (int e = 0; e < 8; e += 2) {
                 bf16x2 p;
@@ -200,15 +213,19 @@ struct SelectArgs {
     int32_t *idx, *cnt;
 };
 
-template <bool SELECT>
-__global__ __launch_bounds__(256, SELECT ? 3 : 4) void search_kernel(
+template <int D, bool SELECT>
+__global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ kb_hi, const uint16_t *__restrict__ kb_lo,
     const float2 *__restrict__ kb_norm, const RowRec *__restrict__ rows_ranked, const int32_t *__restrict__ order,
     int m_total, int n_max, int n_pad, int hq, int hkv, int g, int nchunk, float eps, float *__restrict__ scores,
     SelectArgs sel) {
     extern __shared__ __attribute__((aligned(16))) char smem[];
-    float2 *mbox = reinterpret_cast<float2 *>(smem + kSearchBufs * kSearchTile);
-    float *mtop = reinterpret_cast<float *>(smem + kSearchStageBytes);   // [head] max of the row's pair maxima
+    constexpr int KS = D / 16;            // k-slices of one MFMA row of fragments
+    constexpr int LPW = D / 32;           // wave-wide 1 KB loads per wave and tile (both planes: 4 waves x LPW)
+    constexpr int RPL = kRowsPerLoad<D>;  // pooled-key rows one such load covers
+    constexpr int LPR = kChunks<D>;       // lanes per row
+    float2 *mbox = reinterpret_cast<float2 *>(smem + kSearchBufs * kSearchTile<D>);
+    float *mtop = reinterpret_cast<float *>(smem + kSearchStageBytes<D>);   // [head] max of the row's pair maxima
     float *xchg = mtop + 4;                                              // [wave] prologue exchange: query norm, key norm
     float *ms_all = mtop + kSearchRowHeader / sizeof(float);
 
@@ -229,55 +246,55 @@ __global__ __launch_bounds__(256, SELECT ? 3 : 4) void search_kernel(
     const float2 *knorm = kb_norm + (size_t)bi.kb_row0 * hkv + hk;   // pooled key J of the row: knorm[J * hkv]
 
     // Query fragments: qa[qt][ks] covers queries 64qh + 32qt + l%32, dims 16ks + 8(l/32)..+7.
-    bf16x8 qa[2][8];
+    bf16x8 qa[2][KS];
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         int row = 64 * qh + 32 * qt + (l & 31);
         row = row < bi.q_len ? row : bi.q_len - 1;   // rows past a ragged end are masked in the reduction
-        const uint16_t *qp = Q + ((size_t)(bi.q_tok0 + row) * hq + h) * kHeadDim + 8 * half;
+        const uint16_t *qp = Q + ((size_t)(bi.q_tok0 + row) * hq + h) * D + 8 * half;
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) qa[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
+        for (int ks = 0; ks < KS; ++ks) qa[qt][ks] = *reinterpret_cast<const bf16x8 *>(qp + 16 * ks);
     }
     // Largest pooled-key norm of the row's causal blocks (for the bound on the logits).
     float kmax = 0.f;
     for (int J = tid; J <= I; J += 256) kmax = fmaxf(kmax, knorm[(size_t)J * hkv].x);
 
-    // Tile loads: 16 wave-wide instructions per tile (2 planes x 8 groups of 4 rows), 4 per wave.
-    // Instruction q = 4w + i covers plane q/8, rows 4(q%8) + l/16; lane l fills LDS position l%16
-    // of its row, i.e. fetches global chunk (l%16) ^ (row & 15).  Rows past the diagonal
+    // Tile loads: D/8 wave-wide instructions per tile (2 planes x D/16 groups of 512/D rows), D/32
+    // per wave (head dimension 128: 16 instructions, 4 per wave, 4 rows each).  Instruction
+    // q = LPW w + i covers plane q / (2 LPW), rows RPL (q % (2 LPW)) + l / LPR; lane l fills LDS
+    // position l % LPR of its row, i.e. fetches global chunk (l % LPR) ^ (row & kSwz).  Rows past the diagonal
     // (J > I) are clamped to I: they are computed and dropped.  A row that runs on the hi plane
     // alone does not load the other one (waves 2 and 3 then issue nothing).
     const int ntile = I / 32 + 1;
     const bool ragged = bi.q_len < kBlock;
     const bool hi_only = SELECT && !ragged && ntile > kSearchExactTiles && sel.alpha > 0.f;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(FP_LDS(char) *)smem;
-    const uint32_t row_bytes = (uint32_t)hkv * kHeadDim * 2;
-    const size_t pl_off = ((size_t)bi.kb_row0 * hkv + hk) * kHeadDim * 2;
+    const uint32_t row_bytes = (uint32_t)hkv * D * 2;
+    const size_t pl_off = ((size_t)bi.kb_row0 * hkv + hk) * D * 2;
     const char *pl_base = reinterpret_cast<const char *>(w < 2 ? kb_hi : kb_lo) + pl_off;
-    int ld_row[4];
-    uint32_t ld_col[4];
+    int ld_row[LPW];
+    uint32_t ld_col[LPW];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        ld_row[i] = 4 * ((4 * w + i) & 7) + (l >> 4);
-        ld_col[i] = (uint32_t)(((l & 15) ^ (ld_row[i] & 15)) * 16);
+    for (int i = 0; i < LPW; ++i) {
+        ld_row[i] = RPL * ((LPW * w + i) % (2 * LPW)) + l / LPR;
+        ld_col[i] = (uint32_t)(((l % LPR) ^ (ld_row[i] & kSwz<D>)) * 16);
     }
 #define FP_LOAD_TILE(jt)                                                                                  \
     do {                                                                                                  \
         if (!hi_only || w < 2) {                                                                          \
-            const uint32_t dst_ = lds_base + (uint32_t)(((jt) % kSearchBufs) * kSearchTile) + (w >> 1) * kSearchPlane; \
-            _Pragma("unroll") for (int i_ = 0; i_ < 4; ++i_) {                                            \
+            const uint32_t dst_ = lds_base + (uint32_t)(((jt) % kSearchBufs) * kSearchTile<D>) + (w >> 1) * kSearchPlane<D>; \
+            _Pragma("unroll") for (int i_ = 0; i_ < LPW; ++i_) {                                          \
                 int J_ = 32 * (jt) + ld_row[i_];                                                          \
                 J_ = J_ <= I ? J_ : I;                                                                    \
-                load_to_lds(pl_base, (uint32_t)J_ * row_bytes + ld_col[i_], dst_ + ((4 * w + i_) & 7) * 1024); \
+                load_to_lds(pl_base, (uint32_t)J_ * row_bytes + ld_col[i_], dst_ + ((LPW * w + i_) % (2 * LPW)) * 1024); \
             }                                                                                             \
         }                                                                                                 \
     } while (0)
 
-    // B-fragment address inside a buffer: row l%32, chunk (2ks + half) ^ (row & 15).
+    // B-fragment address inside a buffer: row l%32, chunk (2ks + half) ^ (row & kSwz) = 2ks ^ (half ^ (row & kSwz)).
     const int brow = l & 31;
-    const uint32_t b_frag =
-        (uint32_t)(brow * 256 + ((((brow >> 1) & 7) << 5) | ((half ^ (brow & 1)) << 4)));
-#define FP_BUF(jt) ((uint32_t)(((jt) % kSearchBufs) * kSearchTile))
+    const uint32_t b_frag = (uint32_t)(brow * 2 * D + ((half ^ (brow & kSwz<D>)) << 4));
+#define FP_BUF(jt) ((uint32_t)(((jt) % kSearchBufs) * kSearchTile<D>))
 
     // Prologue: tile 0 (and the older Q and norm loads) landed; the waves exchange their largest
     // query norm (per head) and pooled-key norm (per workgroup).
@@ -288,7 +305,7 @@ __global__ __launch_bounds__(256, SELECT ? 3 : 4) void search_kernel(
         for (int ks = 0; ks < 8; ++ks) asm volatile("" : "+v"(qa[qt][ks]));   // Q has landed before the loop
     FP_WAIT_VMCNT(0);
     {
-        const float qn = sqrtf(search_qnorm2(qa));
+        const float qn = sqrtf(search_qnorm2<D>(qa));
         kmax = wave_max(kmax);
         if (l == 0) {
             xchg[2 * w] = qn;
@@ -324,7 +341,7 @@ __global__ __launch_bounds__(256, SELECT ? 3 : 4) void search_kernel(
         if (jt_ + 1 < ntile) FP_LOAD_TILE(jt_ + 1);                                                       \
         if (active) {                                                                                     \
             f32x16 acc_[2];                                                                               \
-            search_mma<BOTH>(smem, FP_BUF(jt_) + b_frag, qa, acc_);                                       \
+            search_mma<D, BOTH>(smem, FP_BUF(jt_) + b_frag, qa, acc_);                                       \
             const float2 v_ = SMALL ? search_reduce_small(acc_) : search_reduce<RAGGED>(acc_, bi.q_len, 64 * qh, half); \
             if (l < 32) {                                                                                 \
                 if (qh) {                                                                                 \
@@ -434,14 +451,14 @@ __global__ __launch_bounds__(256, SELECT ? 3 : 4) void search_kernel(
             const int n0 = cand0[32], n1 = cand0[36 + 32];
             if (n0 == 0 && n1 == 0) break;
             const int nmine = hd ? n1 : n0;
-            if (nmine > 0) {   // wave qh gathers plane qh of the head's tile: 8 instructions of 4 rows
+            if (nmine > 0) {   // wave qh gathers plane qh of the head's tile: 2 LPW instructions of RPL rows
                 const char *pb = reinterpret_cast<const char *>(qh ? kb_lo : kb_hi) + pl_off;
-                const uint32_t dst = lds_base + (uint32_t)(hd * kSearchTile + qh * kSearchPlane);
+                const uint32_t dst = lds_base + (uint32_t)(hd * kSearchTile<D> + qh * kSearchPlane<D>);
 #pragma unroll
-                for (int i = 0; i < 8; ++i) {
-                    const int row = 4 * i + (l >> 4);
+                for (int i = 0; i < 2 * LPW; ++i) {
+                    const int row = RPL * i + l / LPR;
                     const int J = cand[row];
-                    load_to_lds(pb, (uint32_t)J * row_bytes + (uint32_t)(((l & 15) ^ (row & 15)) * 16), dst + i * 1024);
+                    load_to_lds(pb, (uint32_t)J * row_bytes + (uint32_t)(((l % LPR) ^ (row & kSwz<D>)) * 16), dst + i * 1024);
                 }
             }
             FP_WAIT_VMCNT(0);
@@ -449,7 +466,7 @@ __global__ __launch_bounds__(256, SELECT ? 3 : 4) void search_kernel(
             float2 v = make_float2(-INFINITY, 0.f);
             if (nmine > 0) {
                 f32x16 acc[2];
-                search_mma<true>(smem, (uint32_t)(hd * kSearchTile) + b_frag, qa, acc);
+                search_mma<D, true>(smem, (uint32_t)(hd * kSearchTile<D>) + b_frag, qa, acc);
                 v = small ? search_reduce_small(acc) : search_reduce<false>(acc, bi.q_len, 64 * qh, half);
                 if (qh && l < 32) mbox[hd * 32 + l] = v;
             }

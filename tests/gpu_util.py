@@ -12,12 +12,12 @@ import synth
 # for scores that flush to zero (the GPU's exp2 has no denormal results).
 O_MAX_ABS, O_MEAN_ABS = 2e-2, 2e-3
 SCORE_RTOL, SCORE_ATOL = 5e-4, 1e-30
-# lse: the kernel sums the bf16-rounded probabilities (the values that multiply V).  bf16 keeps 8
-# significant bits, so round-to-nearest is off by at most 2^-8 relative (at the low end of a
-# binade; 2^-9 at the high end): if every term of a row leans the same way, log2 of the row sum
-# is off by log2(1 + 2^-8) = 5.6e-3.  Typical rows are far inside that; a randomised sweep met
-# 4.1e-3 once in 8343 queries.
-LSE_ATOL = 6e-3
+# lse = c*m + log2(sum p): the row sum is taken over the fp32 exponentials (before they are rounded
+# to bf16 for the PV product), so what is left is the fp32 accumulation of the logits (128 exact
+# bf16 x bf16 products each: a few 1e-6 relative of |q||k|), the hardware exp2 / log2 (1 ulp) and
+# the fp32 sum of up to 2^18 terms; logits here reach a few tens, so 5e-4 absolute leaves an
+# order of magnitude of margin over the largest error the randomised sweeps met.
+LSE_ATOL = 5e-4
 BAND = 1e-3           # near-threshold band: |score - alpha*max| <= BAND * alpha*max
 
 

@@ -52,7 +52,7 @@ def test_layout_matches_block_arithmetic(lib):
     ([1, 128], 8, 2, 128, 128, 0.0, B.FP_ERR_INVALID_ARG),     # does not start at 0
     ([0, 128], 0, 1, 128, 128, 0.0, B.FP_ERR_INVALID_ARG),
     ([0, 128], 8, 2, 128, 128, float("nan"), B.FP_ERR_INVALID_ARG),
-    ([0, 128], 8, 2, 64, 128, 0.0, B.FP_ERR_UNSUPPORTED),      # head_dim
+    ([0, 128], 8, 2, 96, 128, 0.0, B.FP_ERR_UNSUPPORTED),      # head_dim other than 64, 128, 256
     ([0, 128], 8, 2, 128, 64, 0.0, B.FP_ERR_UNSUPPORTED),      # block
     ([0, 4097 * 128], 8, 2, 128, 128, 0.0, B.FP_ERR_UNSUPPORTED),  # more than 4096 blocks in a sequence
 ])

@@ -1,0 +1,146 @@
+"""GPU parity at head dimensions 64 and 256 (the kernels are templates over it): every entry point
+against the oracle on the same shapes the head-dimension-128 tests use, through the C ABI."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2603_06199_amd import binding as B
+import synth
+
+from gpu_util import (LSE_ATOL, causal_mask, compare_lists_banded, compare_lists_exact, compare_lists_same_outside_band,
+                      compare_O, compare_scores, dev)
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+CASES = [
+    # name, seqlens, hq, hkv
+    ("tiny_ragged", [5], 2, 2),
+    ("several_tiles", [1536], 8, 2),
+    ("packed_ragged", [640, 77, 1300, 128], 8, 4),
+    ("g8_long_row", [5000], 8, 1),         # more than one pooled-key tile per row
+    ("g3_odd_group", [1100, 300], 6, 2),
+]
+
+
+@pytest.fixture(scope="module", params=[(d, c) for d in (64, 256) for c in CASES],
+                ids=[f"d{d}-{c[0]}" for d in (64, 256) for c in CASES])
+def case(request):
+    d, (name, seqlens, hq, hkv) = request.param
+    w = synth.small(name, seqlens, hq, hkv, seed=13, head_dim=d)
+    Q, K, V = synth.make_qkv(w)
+    cu = w.cu_seqlens
+    print(f"\n[case] head_dim {d} {name} seqlens={seqlens} hq={hq} hkv={hkv}", flush=True)
+    plan = B.Plan(cu, hq, hkv, head_dim=d)
+    out = dict(w=w, d=d, cu=cu, Q=Q, K=K, V=V, plan=plan, dQ=dev(Q), dK=dev(K), dV=dev(V))
+    out["P_ref"] = oracle.block_search(Q, K, cu)
+    yield out
+    plan.close()
+
+
+def test_scores_and_lists(case):
+    plan, w, cu = case["plan"], case["w"], case["cu"]
+    P = plan.fp_block_search(case["dQ"], case["dK"])
+    torch.cuda.synchronize()
+    compare_scores(P.cpu().numpy(), case["P_ref"], cu)
+    for alpha, sink, win in ((w.alpha, 256, 512), (0.3, 100, 200), (0.0, 0, 0)):
+        idx_r, cnt_r = oracle.threshold(case["P_ref"], cu, alpha, sink_tokens=sink, window_tokens=win)
+        idx, cnt = plan.fp_threshold(torch.from_numpy(case["P_ref"]).cuda(), alpha, sink_tokens=sink, window_tokens=win)
+        idx2, cnt2 = plan.fp_threshold(P, alpha, sink_tokens=sink, window_tokens=win)
+        idx_f, cnt_f = plan.fp_search_select(case["dQ"], case["dK"], alpha, sink_tokens=sink, window_tokens=win)
+        torch.cuda.synchronize()
+        compare_lists_exact(idx.cpu().numpy(), cnt.cpu().numpy(), idx_r, cnt_r)
+        compare_lists_banded(idx2.cpu().numpy(), cnt2.cpu().numpy(), case["P_ref"], cu, alpha, sink_tokens=sink, window_tokens=win)
+        compare_lists_exact(idx_f.cpu().numpy(), cnt_f.cpu().numpy(), idx2.cpu().numpy(), cnt2.cpu().numpy())
+
+
+def test_attention(case):
+    w, cu = case["w"], case["cu"]
+    idx_r, cnt_r = oracle.threshold(case["P_ref"], cu, w.alpha)
+    O_ref, lse_ref = oracle.sparse_prefill(case["Q"], case["K"], case["V"], cu, idx_r, cnt_r)
+    O, lse = case["plan"].fp_sparse_prefill(case["dQ"], case["dK"], case["dV"], torch.from_numpy(idx_r).cuda(),
+                                            torch.from_numpy(cnt_r).cuda())
+    torch.cuda.synchronize()
+    compare_O(O, O_ref)
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, atol=LSE_ATOL, rtol=0)
+    Od_ref, lsed_ref = oracle.dense_prefill(case["Q"], case["K"], case["V"], cu)
+    Od, lsed = case["plan"].fp_dense_prefill(case["dQ"], case["dK"], case["dV"])
+    torch.cuda.synchronize()
+    compare_O(Od, Od_ref)
+    np.testing.assert_allclose(lsed.cpu().numpy(), lsed_ref, atol=LSE_ATOL, rtol=0)
+    # threshold disabled: the sparse path visits every causal block and equals the dense one bit for bit
+    idx_a, cnt_a = oracle.threshold(case["P_ref"], cu, 0.0)
+    Oa, lsea = case["plan"].fp_sparse_prefill(case["dQ"], case["dK"], case["dV"], torch.from_numpy(idx_a).cuda(),
+                                              torch.from_numpy(cnt_a).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(Oa.view(torch.int16), Od.view(torch.int16)) and torch.equal(lsea, lsed)
+
+
+def test_random_lists_and_empty_rows(case):
+    cu, hq = case["cu"], case["w"].hq
+    idx, cnt = synth.forced_density_lists(cu, hq, 0.4, seed=3, sink_blocks=0, window_blocks=0)
+    cnt[:, ::5] = 0
+    O_ref, lse_ref = oracle.sparse_prefill(case["Q"], case["K"], case["V"], cu, idx, cnt)
+    O, lse = case["plan"].fp_sparse_prefill(case["dQ"], case["dK"], case["dV"], torch.from_numpy(idx).cuda(),
+                                            torch.from_numpy(cnt).cuda())
+    torch.cuda.synchronize()
+    compare_O(O, O_ref)
+    got, fin = lse.cpu().numpy(), np.isfinite(lse_ref)
+    np.testing.assert_allclose(got[fin], lse_ref[fin], atol=LSE_ATOL, rtol=0)
+    assert np.all(np.isneginf(got[~fin]))
+
+
+@pytest.mark.parametrize("d", [64, 256])
+def test_chunked_prefill_and_long_rows(d):
+    """A prefill chunk after a KV prefix (ragged tail included), and rows of more than 256 key
+    blocks, which the one-pass entry point scores on one plane and re-scores where it matters."""
+    rng = np.random.default_rng(5 + d)
+    kv, q, hq, hkv = [128 * 9 + 60, 640], [128 * 2 + 60, 128], 4, 2
+    cuk = np.concatenate([[0], np.cumsum(kv)]).astype(np.int32)
+    cuq = np.concatenate([[0], np.cumsum(q)]).astype(np.int32)
+    u = rng.standard_normal(d).astype(np.float32); u /= np.linalg.norm(u)
+    Kf = rng.standard_normal((cuk[-1], hkv, d)).astype(np.float32)
+    Kf[256:384] += 3.0 * u
+    Q = synth.f32_to_bf16_bits(rng.standard_normal((cuq[-1], hq, d)).astype(np.float32) + 1.5 * u)
+    K = synth.f32_to_bf16_bits(Kf)
+    V = synth.f32_to_bf16_bits(rng.standard_normal((cuk[-1], hkv, d)).astype(np.float32))
+    plan = B.Plan(cuq, hq, hkv, head_dim=d, cu_seqlens_k=cuk)
+    dQ, dK, dV = dev(Q), dev(K), dev(V)
+    P_ref = oracle.block_search(Q, K, cuq, cu_seqlens_k=cuk)
+    P = plan.fp_block_search(dQ, dK)
+    torch.cuda.synchronize()
+    m, n, ro = oracle.layout(cuq, cu_seqlens_k=cuk)
+    cm = np.zeros((m, n), bool)
+    for s in range(2):
+        pb = (kv[s] - q[s]) // 128
+        for I in range(ro[s + 1] - ro[s]):
+            cm[ro[s] + I, :I + pb + 1] = True
+    np.testing.assert_allclose(P.cpu().numpy()[:, cm], P_ref[:, cm], rtol=5e-4, atol=1e-30)
+    idx_r, cnt_r = oracle.threshold(P_ref, cuq, 0.2, cu_seqlens_k=cuk)
+    O_ref, lse_ref = oracle.sparse_prefill(Q, K, V, cuq, idx_r, cnt_r, cu_seqlens_k=cuk)
+    O, lse = plan.fp_sparse_prefill(dQ, dK, dV, torch.from_numpy(idx_r).cuda(), torch.from_numpy(cnt_r).cuda())
+    Od_ref, _ = oracle.dense_prefill(Q, K, V, cuq, cu_seqlens_k=cuk)
+    Od, _ = plan.fp_dense_prefill(dQ, dK, dV)
+    torch.cuda.synchronize()
+    compare_O(O, O_ref); compare_O(Od, Od_ref)
+    np.testing.assert_allclose(lse.cpu().numpy(), lse_ref, atol=LSE_ATOL, rtol=0)
+    plan.close()
+
+    w = synth.small("long_rows", [128 * 300 + 5], 4, 2, seed=19, head_dim=d)
+    Q, K, _ = synth.make_qkv(w)
+    cu = w.cu_seqlens
+    dQ, dK = dev(Q), dev(K)
+    plan = B.Plan(cu, w.hq, w.hkv, head_dim=d)
+    P_ref = oracle.block_search(Q, K, cu)
+    P = plan.fp_block_search(dQ, dK)
+    torch.cuda.synchronize()
+    compare_scores(P.cpu().numpy(), P_ref, cu)
+    for alpha in (0.12, 0.6, 1.0):
+        idx2, cnt2 = plan.fp_threshold(P, alpha)
+        idx, cnt = plan.fp_search_select(dQ, dK, alpha)
+        torch.cuda.synchronize()
+        nd, nb = compare_lists_banded(idx.cpu().numpy(), cnt.cpu().numpy(), P_ref, cu, alpha)
+        nd2 = compare_lists_same_outside_band(idx.cpu().numpy(), cnt.cpu().numpy(), idx2.cpu().numpy(), cnt2.cpu().numpy(),
+                                              P_ref, causal_mask(cu), alpha)
+        print(f"head_dim {d} alpha {alpha}: kept {int(cnt.sum())}, vs oracle {nd} (band {nb}), vs two calls {nd2}")
+    plan.close()
