@@ -133,10 +133,10 @@ fp_status fp_block_search(fp_plan *plan, const void *Q, const void *K, float eps
  * harnesses that forbid hipMalloc.  Same arguments, same kernels and same results as
  * fp_block_search; the pooled keys of Alg. 1 stage 1 go to a fixed array inside the library
  * (FP_STATIC_SCRATCH_BYTES per GPU) instead of the plan's buffer, so `plan` may be one whose
- * workspace is in use elsewhere.  Limit: (key blocks of the batch) x Hkv x (2 planes x 256 B + 8 B
- * of norms) must fit, i.e. key blocks x Hkv <= 16384 at head_dim 128 (256K tokens at Hkv = 8, 512K at Hkv = 4; half as many
- * at head_dim 256); beyond it the call
- * returns FP_ERR_STATIC_LIMIT and launches nothing.  The call allocates nothing and frees
+ * workspace is in use elsewhere.  Limit: (key blocks of the batch) x Hkv x (2 planes x 2 head_dim
+ * bytes + 8 B of norms) must fit, i.e. key blocks x Hkv <= 16384 at head_dim 128 (256K tokens at
+ * Hkv = 8, 512K at Hkv = 4; half as many at head_dim 256); beyond it the call returns
+ * FP_ERR_STATIC_LIMIT and launches nothing.  The call allocates nothing and frees
  * nothing.  All calls on one GPU share that GPU's array: it needs no clearing (every entry a
  * call reads it has written first), but two calls that may overlap in time on one GPU (different
  * streams, or graphs replayed concurrently) race and must be ordered by the caller.
