@@ -151,7 +151,10 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk
     e1.record()
     torch.cuda.synchronize()
     fused_ms = e0.elapsed_time(e1) / steps
-    assert int(cnt.sum().item()) == kept
+    # long rows are scored on one bf16 plane and re-scored where a decision could hinge: the lists may
+    # differ from the two-call ones on pairs within an ulp or so of the threshold (the tests hold the bar)
+    kept_one_pass = int(cnt.sum().item())
+    assert abs(kept_one_pass - kept) <= max(8, kept // 100000), (kept_one_pass, kept)
 
     T = plan.T
     search_bytes = 2 * d * (T * w.hq + plan.Tk * w.hkv) + 4 * pairs   # Q once + K once + one fp32 per causal pair
@@ -164,7 +167,7 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk
         ms_median=dict(zip(("search", "threshold", "sparse_attention"), map(float, np.median(st, axis=0)))),
         ms_min=dict(zip(("search", "threshold", "sparse_attention"), map(float, st.min(axis=0)))),
         density=kept / pairs, density_per_head_min=float(per_head.min()), density_per_head_max=float(per_head.max()),
-        kept_pairs=kept, causal_pairs=pairs,
+        kept_pairs=kept, kept_pairs_one_pass=kept_one_pass, causal_pairs=pairs,
         speedup_vs_own_dense=(dense_ms / float(search_ms + thr_ms + sparse_ms)) if dense_ms else None,
         speedup_vs_own_dense_fused=(dense_ms / float(fused_ms + sparse_ms)) if dense_ms else None,
         search_gbs=search_bytes / search_ms / 1e6,
@@ -264,6 +267,28 @@ def library_gemm_tflops(torch, n=8192):
     return 2 * n ** 3 / (e0.elapsed_time(e1) / 50) / 1e9
 
 
+def library_copy_gbs(torch, nbytes=2**30):
+    """A plain device copy (torch's copy_ of 1 GiB: reads 1 GiB, writes 1 GiB) and a plain read
+    (a sum over 1 GiB of fp32) on the same box: the HBM rates a streaming kernel reaches here.
+    Context for the search's fraction of the published 8 TB/s."""
+    src = torch.empty(nbytes // 4, dtype=torch.float32, device="cuda").normal_()
+    dst = torch.empty_like(src)
+    out = {}
+    for name, fn, moved in (("copy", lambda: dst.copy_(src), 2 * nbytes), ("read", lambda: src.sum(), nbytes)):
+        for _ in range(3):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(20):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = moved / (e0.elapsed_time(e1) / 20) / 1e6
+    del src, dst
+    return out
+
+
 def calibrate_copy(torch):
     """One plain 1 GiB device copy: a kernel of known size for scaling rocprofv3's byte counters."""
     src = torch.empty(2**28, dtype=torch.float32, device="cuda").normal_()
@@ -338,7 +363,8 @@ def main():
                     help="also time the sparse kernel alone on random causal lists of these densities")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--gemm-reference", action="store_true",
-                    help="also time a library bf16 GEMM (8192^3) as context for the MFMA fractions")
+                    help="also time a library bf16 GEMM (8192^3) and a plain 1 GiB device copy / read as context for the "
+                         "MFMA and HBM fractions")
     ap.add_argument("--chunk", type=int, default=0,
                     help="chunked prefill: time the path for the last CHUNK tokens of every sequence as queries against "
                          "the whole sequence's keys (multiple of 128); prints its own JSON line")
@@ -479,6 +505,7 @@ def main():
         "forced_density": forced or None,
         "alpha_sweep": sweep_a,
         "library_gemm_bf16_tflops": library_gemm_tflops(torch) if a.gemm_reference else None,
+        "library_copy_gbs": library_copy_gbs(torch) if a.gemm_reference else None,
         "supplementary_block_coherent_planting": sup,
         "paper_context": "paper reports 27.78x at 256K and 1.71x at 4K vs FlashAttention 2.8.3 on NVIDIA H20 (real activations, density 3.5% at 256K)",
     }

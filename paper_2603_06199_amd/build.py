@@ -22,6 +22,24 @@ HIPCC_FLAGS = [
 ]
 
 
+# The kernels carry inline assembly whose correctness leans on this compiler's register handling
+# (loads issued from assembly whose results are first touched behind an explicit s_waitcnt, a
+# hand-placed s_nop before v_permlane32_swap): the GPU tests were run with this toolchain, and a
+# different one has to pass them again before its output is trusted.
+TESTED_HIPCC = "7.2"
+
+
+def hipcc_version(hipcc: str) -> str:
+    try:
+        out = subprocess.run([hipcc, "--version"], capture_output=True, text=True).stdout
+        for line in out.splitlines():
+            if line.startswith("HIP version:"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def stale() -> bool:
     if not os.path.exists(LIB):
         return True
@@ -33,6 +51,10 @@ def stale() -> bool:
 def build(force: bool = True, verbose: bool = False) -> str:
     if force or stale():
         hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+        ver = hipcc_version(hipcc)
+        if not ver.startswith(TESTED_HIPCC):
+            print(f"warning: hipcc {ver} is not the tested {TESTED_HIPCC}.x: run the GPU tests before relying on this build",
+                  file=sys.stderr, flush=True)
         cmd = [hipcc] + HIPCC_FLAGS + ["-o", LIB] + [os.path.join(CSRC, s) for s in SOURCES]
         if verbose:
             print(" ".join(cmd), flush=True)

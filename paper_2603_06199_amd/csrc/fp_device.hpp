@@ -100,7 +100,7 @@ __device__ __forceinline__ void load_to_lds(const char *sbase, uint32_t voff, ui
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(voff), "s"(sbase), "s"(lds_addr)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // s_waitcnt vmcnt(n) alone (expcnt and lgkmcnt left at "no wait"), n < 64: the count's low four

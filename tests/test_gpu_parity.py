@@ -216,12 +216,14 @@ def test_custom_softmax_scale_and_eps():
     plan.close()
 
 
-@pytest.mark.parametrize("seqlens,hq,hkv,mode", [
-    ([40000], 4, 2, "coherent"),
-    ([128 * 300 + 5, 128 * 290], 8, 1, "coherent"),     # ragged last q-block of a long row; 4 head pairs per KV head
-    ([36000], 6, 2, "literal"),                          # flat score map: many pairs close to the row max
+@pytest.mark.parametrize("seqlens,hq,hkv,mode,qscale,eps", [
+    ([40000], 4, 2, "coherent", 1, 1e-10),
+    ([128 * 300 + 5, 128 * 290], 8, 1, "coherent", 1, 1e-10),   # ragged last q-block of a long row; 4 head pairs per KV head
+    ([36000], 6, 2, "literal", 1, 1e-10),                        # flat score map: many pairs close to the row max
+    ([40000], 4, 2, "coherent", 16, 1e-10),                      # logits beyond the norm bound: Eq. 1-2 with the pair max
+    ([36000], 4, 2, "literal", 1, 0.5),                          # a visible eps: the pair max is tracked for Eq. 4
 ])
-def test_one_pass_selection_on_long_rows(seqlens, hq, hkv, mode):
+def test_one_pass_selection_on_long_rows(seqlens, hq, hkv, mode, qscale, eps):
     """Rows of more than 256 key blocks: fp_search_select scores them on the pooled key's hi plane and
     re-scores exactly the pairs that may hold the row max or straddle the threshold.  Its lists are
     held to the same rule as the two-call path (equal to the oracle's outside the near-threshold
@@ -229,17 +231,19 @@ def test_one_pass_selection_on_long_rows(seqlens, hq, hkv, mode):
     from gpu_util import causal_mask, compare_lists_same_outside_band
     w = synth.small("long_rows", seqlens, hq, hkv, seed=17, mode=mode)
     Q, K, _ = synth.make_qkv(w)
+    if qscale != 1:      # a power of two: exact in bf16
+        Q = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(Q) * np.float32(qscale))
     cu = w.cu_seqlens
     dQ, dK = dev(Q), dev(K)
     plan = B.Plan(cu, hq, hkv)
-    P_ref = oracle.block_search(Q, K, cu)
-    P = plan.fp_block_search(dQ, dK)
+    P_ref = oracle.block_search(Q, K, cu, eps=eps)
+    P = plan.fp_block_search(dQ, dK, eps=eps)
     torch.cuda.synchronize()
     compare_scores(P.cpu().numpy(), P_ref, cu)
     cm = causal_mask(cu)
     for alpha, sink, win in ((0.12, 256, 512), (0.5, 0, 128), (1.0, 256, 512), (0.97, 0, 0), (3e-3, 0, 0)):
         idx2, cnt2 = plan.fp_threshold(P, alpha, sink_tokens=sink, window_tokens=win)
-        idx, cnt = plan.fp_search_select(dQ, dK, alpha, sink_tokens=sink, window_tokens=win)
+        idx, cnt = plan.fp_search_select(dQ, dK, alpha, sink_tokens=sink, window_tokens=win, eps=eps)
         torch.cuda.synchronize()
         nd, nb = compare_lists_banded(idx.cpu().numpy(), cnt.cpu().numpy(), P_ref, cu, alpha, sink_tokens=sink,
                                       window_tokens=win)

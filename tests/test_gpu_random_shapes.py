@@ -27,20 +27,21 @@ def test_random_shape(seed):
         pb = int(rng.integers(0, 12)) if chunked and rng.random() < 0.7 else 0
         q_lens.append(ql); kv_lens.append(ql + 128 * pb)
     cuq = np.concatenate([[0], np.cumsum(q_lens)]).astype(np.int32); cuk = np.concatenate([[0], np.cumsum(kv_lens)]).astype(np.int32)
+    d = int(rng.choice([64, 128, 128, 256]))
     alpha = float(rng.choice([0.0, 0.05, 0.12, 0.3, 0.9])); sink = int(rng.choice([0, 100, 256, 700])); win = int(rng.choice([0, 128, 512, 1000]))
     tau = float(rng.choice([0.0, 0.05, 0.15]))
     Tk, Tq = int(cuk[-1]), int(cuq[-1])
-    u = rng.standard_normal(128).astype(np.float32); u /= np.linalg.norm(u)
-    Kf = rng.standard_normal((Tk, hkv, 128)).astype(np.float32)
+    u = rng.standard_normal(d).astype(np.float32); u /= np.linalg.norm(u)
+    Kf = rng.standard_normal((Tk, hkv, d)).astype(np.float32)
     for t in rng.choice(Tk, size=max(1, Tk // 400), replace=False):
         lo = (t // 128) * 128; Kf[lo:lo + 128] += 3.0 * u
-    Qf = rng.standard_normal((Tq, hq, 128)).astype(np.float32) + float(rng.choice([0.0, 1.5])) * u
+    Qf = rng.standard_normal((Tq, hq, d)).astype(np.float32) + float(rng.choice([0.0, 1.5])) * u
     Q, K = synth.f32_to_bf16_bits(Qf), synth.f32_to_bf16_bits(Kf)
-    V = synth.f32_to_bf16_bits(rng.standard_normal((Tk, hkv, 128)).astype(np.float32))
-    print(f"\n[random shape {it}] q={q_lens} kv={kv_lens} hq={hq} hkv={hkv} alpha={alpha} sink={sink} win={win} tau={tau}", flush=True)
+    V = synth.f32_to_bf16_bits(rng.standard_normal((Tk, hkv, d)).astype(np.float32))
+    print(f"\n[random shape {it}] q={q_lens} kv={kv_lens} hq={hq} hkv={hkv} d={d} alpha={alpha} sink={sink} win={win} tau={tau}", flush=True)
     ck = cuk if chunked else None
     if not chunked: assert list(cuq) == list(cuk)
-    plan = B.Plan(cuq, hq, hkv, scale=tau, cu_seqlens_k=ck)
+    plan = B.Plan(cuq, hq, hkv, head_dim=d, scale=tau, cu_seqlens_k=ck)
     dQ, dK, dV = dev(Q), dev(K), dev(V)
     tau_o = None if tau == 0.0 else tau
     P_ref = oracle.block_search(Q, K, cuq, tau=tau_o, cu_seqlens_k=ck)
