@@ -39,9 +39,9 @@ def profiled_traffic(workload_tag, kernel):
         for line in open(path):
             if line.startswith("measured:"):
                 measured = line.split(":", 1)[1].strip()
-            tok = line.split()
-            if tok and tok[0] == kernel and len(tok) >= 5:
-                rd, wr = float(tok[-2]) * 2**30, float(tok[-1]) * 2**30
+            if line.startswith(kernel + " "):
+                tok = line[len(kernel):].split()      # dispatches, FETCH KiB, WRITE KiB, read GiB, write GiB, ...
+                rd, wr = float(tok[3]) * 2**30, float(tok[4]) * 2**30
                 # a stored figure from an earlier profiler run of this command, not of this process:
                 # `measured` names the source revision it was taken at
                 return {"bytes": rd + wr, "read_bytes": rd, "write_bytes": wr, "source": os.path.relpath(path, ROOT),
@@ -490,14 +490,14 @@ def main():
         "speedup_vs_own_dense": res["speedup_vs_own_dense"], "speedup_vs_own_dense_fused": res["speedup_vs_own_dense_fused"],
         "roofline": {"bound": "mfma", "kernel": "attn_kernel<sparse>", "achieved": res["sparse_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": res["sparse_tflops"] / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, "fp::attn_kernel<true>") or {}).get("bytes"),
-                     "traffic_detail": profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, "fp::attn_kernel<true>")},
+                     "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, f"fp::attn_kernel<{w.head_dim}, true>") or {}).get("bytes"),
+                     "traffic_detail": profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, f"fp::attn_kernel<{w.head_dim}, true>")},
         "roofline_search": {"bound": "hbm", "kernel": "pool_k_kernel+search_kernel", "achieved": res["search_gbs"],
                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["search_gbs"] / HBM_PEAK_GBS,
                             "mfma_tflops_two_pass": res["search_mfma_tflops"],
                             "mfma_frac_two_pass": res["search_mfma_tflops"] / MFMA_BF16_PEAK_TFLOPS,
                             "exp2_per_s": res["search_exp2_per_s"],
-                            "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, "fp::search_kernel<false>") or {}).get("bytes")},
+                            "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, f"fp::search_kernel<{w.head_dim}, false>") or {}).get("bytes")},
         "roofline_dense": {"bound": "mfma", "kernel": "attn_kernel<dense>", "achieved": res["dense_tflops"],
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": (res["dense_tflops"] or 0) / MFMA_BF16_PEAK_TFLOPS},
