@@ -105,7 +105,7 @@ constexpr int kSearchRowHeader = 64;                   // per-head row maxima an
 constexpr int kSearchCandBytes = kSearchHeads * (32 + 4) * 4;   // SELECT: candidate tile indices + count per head
 constexpr float kSearchSafeLogit = 100.f;              // |x| below this: 2^x needs no reference point in fp32
 constexpr float kSearchEpsNoop = 0x1p-26f;             // eps below this cannot change an fp32 row total >= 1
-constexpr int kSearchExactTiles = 8;                   // SELECT: rows of up to this many tiles run both planes throughout
+constexpr int kSearchExactTiles = 4;                   // SELECT: rows of up to this many tiles run both planes throughout
 
 // 64 x 32 logits of one pooled-key tile: acc[qt] = Q[qt] (hi + lo)^T, or Q[qt] hi^T.  baddr =
 // buffer base + the lane's row and swizzled chunk for k-slice 0; slice ks (dims 16ks..16ks+15, chunks
@@ -413,6 +413,25 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
         }
         const float thr_lo = lo_t + la - 0x1p-14f, thr_hi = hi_t + la + 0x1p-14f;
         int J_scan = 0;
+        // If no pair that the threshold decides (sink and window blocks are kept anyway) has an
+        // interval that meets [T_lo, T_hi] + log2 alpha, every decision already has a margin against
+        // any T in [T_lo, T_hi]: nothing is re-scored, not even the pairs that may hold the max, and
+        // the row's approximate max stands in for T below.
+        if (active && qh == 0) {
+            bool hinge = false;
+            float t_apx = -INFINITY;
+            for (int J = l; J <= I; J += 64) {
+                const float tj = ms[J];
+                const float ej = qn * knorm[(size_t)J * hkv].y + slack;
+                const bool structural = (J < sel.sinkB) || (I - J < sel.winB);
+                hinge |= !structural && tj + ej >= thr_lo && tj - ej <= thr_hi;
+                t_apx = fmaxf(t_apx, tj);
+            }
+            if (__ballot(hinge) == 0ull) {
+                J_scan = I + 1;
+                T_exact = t_apx;   // reduced over the wave after the loop
+            }
+        }
         for (;;) {
             if (qh == 0) {
                 int have = 0, first = 0;

@@ -55,7 +55,7 @@ def _mask_from_lists(idx, cnt):
 
 
 def _lists_same_outside_band(idx_a, cnt_a, idx_b, cnt_b, P, alpha):
-    """Every row, on the GPU: the lists of the one-pass entry point (long rows are scored on one
+    """Every row, on the GPU: the lists of the one-pass entry point (rows of more than 128 key blocks are scored on one
     bf16 plane and re-scored where a decision could hinge) and of the two calls may differ only on
     pairs whose score lies within BAND (relative) of alpha * row max.  P holds zeros above the
     diagonal, so its row max is the causal one."""

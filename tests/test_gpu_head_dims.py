@@ -92,7 +92,7 @@ def test_random_lists_and_empty_rows(case):
 
 @pytest.mark.parametrize("d", [64, 256])
 def test_chunked_prefill_and_long_rows(d):
-    """A prefill chunk after a KV prefix (ragged tail included), and rows of more than 256 key
+    """A prefill chunk after a KV prefix (ragged tail included), and rows of more than 128 key
     blocks, which the one-pass entry point scores on one plane and re-scores where it matters."""
     rng = np.random.default_rng(5 + d)
     kv, q, hq, hkv = [128 * 9 + 60, 640], [128 * 2 + 60, 128], 4, 2

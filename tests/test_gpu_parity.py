@@ -224,7 +224,7 @@ def test_custom_softmax_scale_and_eps():
     ([36000], 4, 2, "literal", 1, 0.5),                          # a visible eps: the pair max is tracked for Eq. 4
 ])
 def test_one_pass_selection_on_long_rows(seqlens, hq, hkv, mode, qscale, eps):
-    """Rows of more than 256 key blocks: fp_search_select scores them on the pooled key's hi plane and
+    """Rows of more than 128 key blocks: fp_search_select scores them on the pooled key's hi plane and
     re-scores exactly the pairs that may hold the row max or straddle the threshold.  Its lists are
     held to the same rule as the two-call path (equal to the oracle's outside the near-threshold
     band) and may differ from the two-call lists only inside that band."""
