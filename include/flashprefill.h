@@ -156,11 +156,17 @@ fp_status fp_threshold(fp_plan *plan, const float *scores, const fp_params *para
 
 /*
  * Stages (i) + (ii) in one pass: the lists fp_threshold would emit from fp_block_search's scores,
- * without the scores ever reaching memory.  Each row's normalised scores are formed in on-chip
- * memory with the same fp32 arithmetic and compared with alpha * their max there, so idx and cnt
- * are identical to those of the two calls in a row (Alg. 1 stage 3 feeding Alg. 2; the paper's
- * Appendix B keeps the two apart, this entry point is the shortcut its Sec. 3.4 decision rule
- * allows because the rule only looks at one row at a time).  Arguments as in the two calls.
+ * without the scores ever reaching memory (Alg. 1 stage 3 feeding Alg. 2; the paper's Appendix B
+ * keeps the two apart, this entry point is the shortcut its Sec. 3.4 decision rule allows because
+ * the rule only looks at one row at a time).  Rows of up to 128 key blocks, ragged q-blocks and
+ * alpha <= 0 are computed exactly as the two calls compute them and give identical idx and cnt.
+ * Longer rows are scored with half the matrix work (one bf16 plane of the pooled key, which
+ * bounds each pair's error), and every pair on which a decision could hinge, that is every pair
+ * that may hold the row maximum or whose error interval meets the threshold, is then re-scored
+ * exactly; all other pairs are decided with a margin.  The lists are therefore those of exact
+ * scores, and can differ from the two-call lists only where a normalised score lies within a few
+ * units in the last place of alpha * max (fp32 rounding of the two normalisations).
+ * Arguments as in the two calls.
  */
 fp_status fp_search_select(fp_plan *plan, const void *Q, const void *K, float eps, const fp_params *params,
                            int32_t *idx, int32_t *cnt, void *hip_stream);
