@@ -59,7 +59,7 @@ def causal_pairs(row_offset, hq, cu=None, cuk=None):
     return int((n * (n + 1) // 2 + n * pb).sum()) * hq
 
 
-def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk=0):
+def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk=0, block=128):
     """Times the path on one workload; returns a dict of measurements (times in ms).  With
     min_timed_ms > 0 (the length sweep) short workloads take more warm-up and timed steps, so that
     the timed region lasts at least that long and the clocks have settled.  chunk > 0: chunked
@@ -78,10 +78,12 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk
         Q = np.ascontiguousarray(np.concatenate([Q[cuk[i + 1] - qlen[i]:cuk[i + 1]] for i in range(len(qlen))]))
         cu = np.concatenate([[0], np.cumsum(qlen)]).astype(np.int32)
     dQ, dK, dV = B.to_device_bf16(Q), B.to_device_bf16(K), B.to_device_bf16(V)
-    plan = B.Plan(cu, w.hq, w.hkv, head_dim=w.head_dim, cu_seqlens_k=cuk)
+    plan = B.Plan(cu, w.hq, w.hkv, head_dim=w.head_dim, block=block, cu_seqlens_k=cuk)
     hq, m, n = w.hq, plan.m_total, plan.n_max
     d = w.head_dim
-    pair_flops = PAIR_FLOPS * d // 128
+    pair_flops = 4 * block * block * d          # QK^T + PV of one (q-block, k-block) visit
+    if block != 128 and chunk > 0:
+        raise SystemExit("--chunk is measured at block 128 only")
     scores = torch.empty((hq, m, n), dtype=torch.float32, device="cuda")
     idx = torch.empty((hq, m, n), dtype=torch.int32, device="cuda")
     cnt = torch.empty((hq, m), dtype=torch.int32, device="cuda")
@@ -173,18 +175,18 @@ def run_workload(w, steps, warmup, dense_runs, torch, B, min_timed_ms=0.0, chunk
         search_gbs=search_bytes / search_ms / 1e6,
         # the one-pass entry point writes lists instead of the score map: Q + K once, 4 B per kept pair and per row
         search_select_gbs=(2 * d * (T * w.hq + plan.Tk * w.hkv) + 4 * kept + 4 * hq * m) / fused_ms / 1e6,
-        search_mfma_tflops=pairs * 2 * 128 * d * 2 / search_ms / 1e9,   # two bf16 passes (hi, lo) per pair
-        search_exp2_per_s=pairs * 128 / (search_ms * 1e-3),                # one exponential per (query, pooled key)
+        search_mfma_tflops=pairs * 2 * block * d * 2 / search_ms / 1e9,   # two bf16 passes (hi, lo) per pair
+        search_exp2_per_s=pairs * block / (search_ms * 1e-3),              # one exponential per (query, pooled key)
         threshold_gbs=thr_bytes / thr_ms / 1e6,
         sparse_tflops=kept * pair_flops / sparse_ms / 1e9,
         dense_tflops=(pairs * pair_flops / dense_ms / 1e9) if dense_ms else None,
-        head_dim=d,
+        head_dim=d, block=block,
     )
     host = dict(Q=Q, K=K, V=V, cu=cu, idx=idx, cnt=cnt, O=O, scores=scores, plan=plan, dQ=dQ, dK=dK, dV=dV)
     return res, host
 
 
-def forced_density_run(w, host, density, steps, torch):
+def forced_density_run(w, host, density, steps, torch, block=128):
     """Sparse kernel alone on random causal lists (sink and window blocks always kept) of a target
     density: the measurement shape of the paper's block-sparse latency table."""
     plan = host["plan"]
@@ -195,7 +197,7 @@ def forced_density_run(w, host, density, steps, torch):
     J = torch.arange(n, device="cuda")[None, :]
     g = torch.Generator(device="cuda"); g.manual_seed(1234)
     for h in range(hq):
-        keep = (torch.rand((m, n), device="cuda", generator=g) < density) | (J < 2) | ((I - J >= 0) & (I - J < 4))
+        keep = (torch.rand((m, n), device="cuda", generator=g) < density) | (J < -(-256 // block)) | ((I - J >= 0) & (I - J < -(-512 // block)))
         keep &= J <= I
         idx[h] = torch.sort((~keep).to(torch.uint8), dim=-1, stable=True).indices.int()
         cnt[h] = keep.sum(-1).int()
@@ -213,7 +215,7 @@ def forced_density_run(w, host, density, steps, torch):
     ms = e0.elapsed_time(e1) / steps
     pairs = causal_pairs(plan.row_offset, hq)
     return dict(target_density=density, density=kept / pairs, sparse_attention_ms=ms,
-                sparse_tflops=kept * (PAIR_FLOPS * w.head_dim // 128) / ms / 1e9)
+                sparse_tflops=kept * (4 * block * block * w.head_dim) / ms / 1e9)
 
 
 def alpha_sweep(w, host, steps, torch, factors=(0.5, 1.0, 2.0)):
@@ -408,6 +410,8 @@ def main():
                          "speedup over the own dense kernel, and the sparse kernel alone at forced 60 %% / 6 %% density")
     ap.add_argument("--head-dim", type=int, default=128, choices=[64, 128, 256],
                     help="head dimension of the synthetic layer (the configurations are stated at 128)")
+    ap.add_argument("--block", type=int, default=128, choices=[64, 128, 256],
+                    help="block size (the paper's and the configurations' is 128; 64 and 256 need head dimension 128)")
     ap.add_argument("--lengths", type=int, nargs="*", default=[], help="with --sweep: only these token counts")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also launch one plain 1 GiB device copy (a known-size kernel for scaling rocprofv3 byte counters)")
@@ -428,6 +432,8 @@ def main():
     torch.cuda.set_device(0)
 
     import dataclasses
+    if a.block != 128 and not a.sweep:
+        raise SystemExit("--block other than 128 is measured with --sweep (the configurations are stated at block 128)")
     if a.sweep:
         rows = []
         # densities the paper reports for this model at each length (its density table; real activations)
@@ -435,9 +441,9 @@ def main():
         for L in (a.lengths or (4096, 8192, 16384, 32768, 65536, 131072, 262144, 524288)):
             wl = dataclasses.replace(synth.config(1, "coherent"), seqlens=(L,), name=f"qwen3_shape_{L // 1024}k_coherent",
                                      head_dim=a.head_dim)
-            r, h = run_workload(wl, a.steps, a.warmup, dense_runs=2, torch=torch, B=B, min_timed_ms=100.0)
+            r, h = run_workload(wl, a.steps, a.warmup, dense_runs=2, torch=torch, B=B, min_timed_ms=100.0, block=a.block)
             dens = (0.6, 0.06) + ((paper_density[L],) if L in paper_density else ())
-            r["forced_density"] = [forced_density_run(wl, h, d, r["timed_steps"], torch) for d in dens]
+            r["forced_density"] = [forced_density_run(wl, h, d, r["timed_steps"], torch, block=a.block) for d in dens]
             r["search_hbm_frac"] = r["search_gbs"] / HBM_PEAK_GBS
             r["search_select_hbm_frac"] = r["search_select_gbs"] / HBM_PEAK_GBS
             log(f"[bench] sweep {json.dumps(r)}")
@@ -448,7 +454,7 @@ def main():
             calibrate_copy(torch)
         print(json.dumps({"metric": "sparse prefill ms/layer vs length (sweep)", "unit": "ms/layer", "n_gpus": 1,
                           "steps": a.steps, "warmup": a.warmup, "dtype": "bf16", "data": "synthetic",
-                          "config": {"workload": f"Qwen3-30B-A3B attention shape (Hq=32, Hkv=4, d={a.head_dim}), block-coherent planting, "
+                          "config": {"workload": f"Qwen3-30B-A3B attention shape (Hq=32, Hkv=4, d={a.head_dim}), block {a.block}, block-coherent planting, "
                                                  "alpha=0.12, 4K..512K tokens"},
                           "paper_context": "paper (NVIDIA H20, real activations): speedup vs FlashAttention 1.71/2.79/4.48/6.94/11.45/18.67/27.78x "
                                            "at 4K..256K; densities 70.4/46.0/29.0/17.6/10.0/5.8/3.5 %",

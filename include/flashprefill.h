@@ -22,7 +22,7 @@
  *     prefill (the queries are the last q_len tokens of a sequence whose first kv_len - q_len
  *     keys were produced earlier): query i of the chunk sits at position prefix + i and sees
  *     keys 0 .. prefix + i; prefix = kv_len - q_len must be a multiple of `block`.
- *   - Blocks of `block` (=128) tokens are aligned to the start of each sequence; a sequence
+ *   - Blocks of `block` tokens (128 in the paper) are aligned to the start of each sequence; a sequence
  *     of kv_len keys has ceil(kv_len / block) key blocks, the last one possibly partial.
  *     Query-block row r = row_offset[s] + I addresses q-block I of sequence s's chunk, which
  *     is block I + prefix / block of the sequence: wherever a comment below says "J <= I",
@@ -52,7 +52,7 @@ extern "C" {
 typedef enum {
     FP_OK = 0,
     FP_ERR_INVALID_ARG = 1, /* null pointer, inconsistent shape, bad cu_seqlens            */
-    FP_ERR_UNSUPPORTED = 2, /* head_dim not 64/128/256, block != 128, over 4096 blocks/seq, or a */
+    FP_ERR_UNSUPPORTED = 2, /* (head_dim, block) not one of (64|128|256, 128), (128, 64|256); over 4096 blocks/seq; or a */
                             /* KV prefix that is not a multiple of the block                */
     FP_ERR_DEVICE = 3,      /* HIP runtime error (no device, allocation or launch failure) */
     FP_ERR_NOMEM = 4,       /* host allocation failed                                      */
@@ -68,7 +68,7 @@ typedef struct {
     const int32_t *cu_seqlens; /* HOST, nseq+1 entries, [0] = 0, strictly increasing          */
     int32_t hq, hkv;           /* query heads, KV heads; hq % hkv == 0                        */
     int32_t head_dim;          /* 64, 128 or 256                                              */
-    int32_t block;             /* 128 (Appendix A: uniform block size)                        */
+    int32_t block;             /* 128 (Appendix A: uniform block size); 64 and 256 at head_dim 128 */
     float scale;               /* softmax scale tau; <= 0 selects 1/sqrt(head_dim)            */
     const int32_t *cu_seqlens_k; /* HOST, nseq+1 entries, or NULL (= cu_seqlens): key-side      */
                                /* lengths for chunked prefill, kv_len >= q_len per sequence   */

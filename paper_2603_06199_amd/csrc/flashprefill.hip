@@ -62,7 +62,10 @@ fp_status check_shape(const fp_shape *s, Layout *out) {
     for (int i = 0; i < s->nseq; ++i)
         if (s->cu_seqlens[i + 1] <= s->cu_seqlens[i] || cuk[i + 1] <= cuk[i]) return FP_ERR_INVALID_ARG;
     if (!(s->scale == s->scale) || std::isinf(s->scale)) return FP_ERR_INVALID_ARG;
-    if ((s->head_dim != 64 && s->head_dim != 128 && s->head_dim != 256) || s->block != fp::kBlock) return FP_ERR_UNSUPPORTED;
+    // head dimension 64 / 128 / 256 at block 128; block 64 / 256 at head dimension 128
+    if (!(((s->head_dim == 64 || s->head_dim == 256) && s->block == 128) ||
+          (s->head_dim == 128 && (s->block == 64 || s->block == 128 || s->block == 256))))
+        return FP_ERR_UNSUPPORTED;
     Layout L;
     L.row_offset.assign((size_t)s->nseq + 1, 0);
     L.kb_offset.assign((size_t)s->nseq + 1, 0);
@@ -86,23 +89,27 @@ fp_status check_shape(const fp_shape *s, Layout *out) {
     return FP_OK;
 }
 
-int search_stage_bytes(int head_dim) {
-    return head_dim == 64 ? fp::kSearchStageBytes<64> : head_dim == 128 ? fp::kSearchStageBytes<128> : fp::kSearchStageBytes<256>;
+int search_stage_bytes(int head_dim, int block) {
+    if (head_dim == 64) return fp::kSearchStageBytes<64, 128>;
+    if (head_dim == 256) return fp::kSearchStageBytes<256, 128>;
+    return block == 64 ? fp::kSearchStageBytes<128, 64> : block == 128 ? fp::kSearchStageBytes<128, 128> : fp::kSearchStageBytes<128, 256>;
 }
+int search_heads_per_wg(int block) { return block == 64 ? 4 : block == 128 ? 2 : 1; }
 int attn_lds_bytes(int head_dim) {
     return head_dim == 64 ? fp::kAttnLds<64> : head_dim == 128 ? fp::kAttnLds<128> : fp::kAttnLds<256>;
 }
 
-template <int D>
+template <int D, int BLK>
 bool set_lds_ceilings() {
-    const int search_lds_max = fp::kSearchStageBytes<D> + fp::kSearchRowHeader + fp::kSearchHeads * kMaxBlocksPerSeq * (int)sizeof(float) + fp::kSearchCandBytes;
-    bool ok = hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<D, false>),
+    const int search_lds_max = fp::kSearchStageBytes<D, BLK> + fp::kSearchRowHeader +
+                               fp::kSearchHeads<BLK> * kMaxBlocksPerSeq * (int)sizeof(float) + fp::kSearchCandBytes;
+    bool ok = hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<D, BLK, false>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, search_lds_max) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<D, true>),
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<D, BLK, true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, search_lds_max) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<D, true>),
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<D, BLK, true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds<D>) == hipSuccess;
-    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<D, false>),
+    ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<D, BLK, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds<D>) == hipSuccess;
     return ok;
 }
@@ -112,7 +119,7 @@ bool set_lds_ceilings() {
 struct fp_plan {
     int device = 0;
     int nseq = 0, hq = 0, hkv = 0, g = 0, T = 0;   // T: query tokens
-    int head_dim = 0;
+    int head_dim = 0, block = 0;
     int m_total = 0, n_max = 0, kb_total = 0;
     float c = 0.f;                    // tau * log2(e)
     fp::RowRec *d_rows = nullptr;     // [m_total]
@@ -164,7 +171,7 @@ const char *fp_status_string(fp_status s) {
     switch (s) {
         case FP_OK: return "ok";
         case FP_ERR_INVALID_ARG: return "invalid argument";
-        case FP_ERR_UNSUPPORTED: return "unsupported shape (head_dim must be 64, 128 or 256, block 128, at most 4096 blocks per sequence, a KV prefix a multiple of the block)";
+        case FP_ERR_UNSUPPORTED: return "unsupported shape (head_dim 64, 128 or 256 with block 128, or head_dim 128 with block 64 or 256; at most 4096 blocks per sequence; a KV prefix a multiple of the block)";
         case FP_ERR_DEVICE: return "HIP device error";
         case FP_ERR_NOMEM: return "out of host memory";
         case FP_ERR_STATIC_LIMIT:
@@ -226,6 +233,7 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
     p->hkv = shape->hkv;
     p->g = shape->hq / shape->hkv;
     p->head_dim = shape->head_dim;
+    p->block = shape->block;
     p->T = shape->cu_seqlens[shape->nseq];
     p->m_total = L.m_total;
     p->n_max = L.n_max;
@@ -233,7 +241,8 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
     const float tau = shape->scale > 0.f ? shape->scale : 1.0f / std::sqrt((float)shape->head_dim);
     p->c = tau * fp::kLog2e;
     p->n_pad = (L.n_max + 31) / 32 * 32;
-    p->search_lds = (size_t)search_stage_bytes(shape->head_dim) + fp::kSearchRowHeader + (size_t)fp::kSearchHeads * p->n_pad * sizeof(float) + fp::kSearchCandBytes;
+    p->search_lds = (size_t)search_stage_bytes(shape->head_dim, shape->block) + fp::kSearchRowHeader +
+                    (size_t)search_heads_per_wg(shape->block) * p->n_pad * sizeof(float) + fp::kSearchCandBytes;
 
     const int32_t *cuk = shape->cu_seqlens_k ? shape->cu_seqlens_k : shape->cu_seqlens;
     std::vector<fp::RowRec> rows((size_t)L.m_total);
@@ -242,10 +251,10 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
         const int a = shape->cu_seqlens[s], b = shape->cu_seqlens[s + 1];
         for (int r = L.row_offset[s]; r < L.row_offset[s + 1]; ++r) {
             const int Iq = r - L.row_offset[s];
-            const int t0 = a + Iq * fp::kBlock;
+            const int t0 = a + Iq * shape->block;
             fp::RowRec rec;
             rec.q_tok0 = t0;
-            rec.q_len = std::min(fp::kBlock, b - t0);
+            rec.q_len = std::min(shape->block, b - t0);
             rec.I = Iq + L.prefix_blocks[s];
             rec.kb_row0 = L.kb_offset[s];
             rec.k_tok0 = cuk[s];
@@ -255,8 +264,8 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
             rows[(size_t)r] = rec;
         }
         for (int j = L.kb_offset[s]; j < L.kb_offset[s + 1]; ++j) {
-            const int t0 = cuk[s] + (j - L.kb_offset[s]) * fp::kBlock;
-            kblk[(size_t)j] = make_int2(t0, std::min(fp::kBlock, cuk[s + 1] - t0));
+            const int t0 = cuk[s] + (j - L.kb_offset[s]) * shape->block;
+            kblk[(size_t)j] = make_int2(t0, std::min(shape->block, cuk[s + 1] - t0));
         }
     }
     // Heaviest rows first: a row's work grows with the number of its causal key blocks.
@@ -294,7 +303,8 @@ fp_status fp_plan_create_in(const fp_shape *shape, int device, void *workspace, 
     ok = ok && hipMemcpy(p->d_rows_ranked, rows_ranked.data(), rows.size() * sizeof(fp::RowRec), hipMemcpyHostToDevice) == hipSuccess;
     // The dynamic-LDS ceilings are per kernel, not per plan: they are set to what the largest
     // supported shape needs, so that plans of different sizes can be alive together.
-    ok = ok && set_lds_ceilings<64>() && set_lds_ceilings<128>() && set_lds_ceilings<256>();
+    ok = ok && set_lds_ceilings<64, 128>() && set_lds_ceilings<128, 64>() && set_lds_ceilings<128, 128>() &&
+         set_lds_ceilings<128, 256>() && set_lds_ceilings<256, 128>();
     const int thr_lds_max = fp::kThresholdWaves * kMaxBlocksPerSeq * (int)sizeof(float);
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::threshold_kernel<true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, thr_lds_max) == hipSuccess;
@@ -319,21 +329,21 @@ static bool on_plan_device(const fp_plan *p) {
 }
 
 extern "C++" {
-template <int D>
+template <int D, int BLK>
 static fp_status launch_search_d(fp_plan *p, const void *Q, const void *K, float eps, float *scores,
                                  const fp::SelectArgs *sel, hipStream_t st, uint16_t *kb_hi, uint16_t *kb_lo,
                                  float2 *kb_norm) {
     fp::pool_k_kernel<D><<<dim3(p->kb_total, p->hkv), 256, 0, st>>>(static_cast<const uint16_t *>(K), p->d_kblk, p->hkv,
                                                                      p->c, kb_hi, kb_lo, kb_norm);
-    const int nchunk = (p->g + fp::kSearchHeads - 1) / fp::kSearchHeads;
+    const int nchunk = (p->g + fp::kSearchHeads<BLK> - 1) / fp::kSearchHeads<BLK>;
     const dim3 grid(p->m_total * p->hkv * nchunk);
     const uint16_t *q = static_cast<const uint16_t *>(Q);
     if (sel != nullptr)
-        fp::search_kernel<D, true><<<grid, 256, p->search_lds, st>>>(q, kb_hi, kb_lo, kb_norm, p->d_rows_ranked, p->d_order,
+        fp::search_kernel<D, BLK, true><<<grid, 256, p->search_lds, st>>>(q, kb_hi, kb_lo, kb_norm, p->d_rows_ranked, p->d_order,
                                                                      p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
                                                                      eps, nullptr, *sel);
     else
-        fp::search_kernel<D, false><<<grid, 256, p->search_lds, st>>>(q, kb_hi, kb_lo, kb_norm, p->d_rows_ranked, p->d_order,
+        fp::search_kernel<D, BLK, false><<<grid, 256, p->search_lds, st>>>(q, kb_hi, kb_lo, kb_norm, p->d_rows_ranked, p->d_order,
                                                                       p->m_total, p->n_max, p->n_pad, p->hq, p->hkv, p->g, nchunk,
                                                                       eps, scores, fp::SelectArgs{});
     return launch_status();
@@ -352,9 +362,14 @@ static fp_status launch_search(fp_plan *p, const void *Q, const void *K, float e
     }
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     switch (p->head_dim) {
-        case 64: return launch_search_d<64>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
-        case 128: return launch_search_d<128>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
-        default: return launch_search_d<256>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
+        case 64: return launch_search_d<64, 128>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
+        case 256: return launch_search_d<256, 128>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
+        default: break;
+    }
+    switch (p->block) {
+        case 64: return launch_search_d<128, 64>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
+        case 256: return launch_search_d<128, 256>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
+        default: return launch_search_d<128, 128>(p, Q, K, eps, scores, sel, st, kb_hi, kb_lo, kb_norm);
     }
 }
 
@@ -385,8 +400,8 @@ fp_status fp_search_select(fp_plan *p, const void *Q, const void *K, float eps, 
         return FP_ERR_INVALID_ARG;
     fp::SelectArgs sel;
     sel.alpha = params->alpha;
-    sel.sinkB = (params->sink_tokens + fp::kBlock - 1) / fp::kBlock;
-    sel.winB = (params->window_tokens + fp::kBlock - 1) / fp::kBlock;
+    sel.sinkB = (params->sink_tokens + p->block - 1) / p->block;
+    sel.winB = (params->window_tokens + p->block - 1) / p->block;
     sel.idx = idx;
     sel.cnt = cnt;
     return launch_search(p, Q, K, eps, nullptr, &sel, hip_stream);
@@ -397,8 +412,8 @@ fp_status fp_threshold(fp_plan *p, const float *scores, const fp_params *params,
     if (p == nullptr || scores == nullptr || idx == nullptr || cnt == nullptr || !params_ok(params))
         return FP_ERR_INVALID_ARG;
     if (!on_plan_device(p)) return FP_ERR_DEVICE;
-    const int sinkB = (params->sink_tokens + fp::kBlock - 1) / fp::kBlock;
-    const int winB = (params->window_tokens + fp::kBlock - 1) / fp::kBlock;
+    const int sinkB = (params->sink_tokens + p->block - 1) / p->block;
+    const int winB = (params->window_tokens + p->block - 1) / p->block;
     const int rows = p->hq * p->m_total;
     const int n_pad = (p->n_max + 63) / 64 * 64;
     const dim3 grid((rows + fp::kThresholdWaves - 1) / fp::kThresholdWaves);
@@ -414,19 +429,19 @@ fp_status fp_threshold(fp_plan *p, const float *scores, const fp_params *params,
 }
 
 extern "C++" {
-template <int D>
+template <int D, int BLK>
 static fp_status launch_attn_d(fp_plan *p, bool sparse, const void *Q, const void *K, const void *V, const int32_t *idx,
                                const int32_t *cnt, void *O, float *lse, hipStream_t st) {
     const int n_super = p->m_total * p->hkv;
-    const int grid = (n_super + 7) / 8 * 8 * p->g;
+    const int grid = (n_super + 7) / 8 * 8 * p->g * (BLK > 128 ? BLK / 128 : 1);   // a 256-query block takes two workgroups
     const uint16_t *q = static_cast<const uint16_t *>(Q), *k = static_cast<const uint16_t *>(K),
                    *v = static_cast<const uint16_t *>(V);
     uint16_t *o = static_cast<uint16_t *>(O);
     if (sparse)
-        fp::attn_kernel<D, true><<<dim3(grid), 256, fp::kAttnLds<D>, st>>>(q, k, v, idx, cnt, p->d_rows_ranked, p->d_order, p->m_total,
+        fp::attn_kernel<D, BLK, true><<<dim3(grid), 256, fp::kAttnLds<D>, st>>>(q, k, v, idx, cnt, p->d_rows_ranked, p->d_order, p->m_total,
                                                                           p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     else
-        fp::attn_kernel<D, false><<<dim3(grid), 256, fp::kAttnLds<D>, st>>>(q, k, v, nullptr, nullptr, p->d_rows_ranked, p->d_order,
+        fp::attn_kernel<D, BLK, false><<<dim3(grid), 256, fp::kAttnLds<D>, st>>>(q, k, v, nullptr, nullptr, p->d_rows_ranked, p->d_order,
                                                                            p->m_total, p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     return launch_status();
 }
@@ -437,9 +452,14 @@ static fp_status launch_attn(fp_plan *p, bool sparse, const void *Q, const void 
     if (!on_plan_device(p)) return FP_ERR_DEVICE;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     switch (p->head_dim) {
-        case 64: return launch_attn_d<64>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
-        case 128: return launch_attn_d<128>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
-        default: return launch_attn_d<256>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
+        case 64: return launch_attn_d<64, 128>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
+        case 256: return launch_attn_d<256, 128>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
+        default: break;
+    }
+    switch (p->block) {
+        case 64: return launch_attn_d<128, 64>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
+        case 256: return launch_attn_d<128, 256>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
+        default: return launch_attn_d<128, 128>(p, sparse, Q, K, V, idx, cnt, O, lse, st);
     }
 }
 

@@ -62,10 +62,14 @@ __device__ __forceinline__ s16x4 lds_read_tr(const char *p) {
  * head, so one head's K and V (128 MiB each at 512K tokens) are what the last-level cache holds
  * at a time, not every head's.
  */
-template <bool SPARSE>
-__device__ __forceinline__ int attn_tile_block(const int32_t *list, int t, int I) {
-    if (!SPARSE) return t >> 1;
-    const int b = list[t >> 1];
+// Block of 64-key tile t: entry t / TPB of the list (TPB tiles per block), the entry index kept
+// below nb and the block id inside [0, I].
+template <bool SPARSE, int TPB>
+__device__ __forceinline__ int attn_tile_block(const int32_t *list, int t, int I, int nb) {
+    int li = t / TPB;
+    li = li < nb ? li : nb - 1;
+    if (!SPARSE) return li;
+    const int b = list[li];
     return b < 0 ? 0 : (b > I ? I : b);
 }
 
@@ -166,7 +170,7 @@ __device__ __forceinline__ void attn_pv(const char *smem, const uint32_t (&vaddr
             }
 }
 
-template <int D, bool SPARSE>
+template <int D, int BLK, bool SPARSE>
 __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ cnt, const RowRec *__restrict__ rows_ranked,
@@ -179,8 +183,11 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     constexpr int RPL = kRowsPerLoad<D>;  // rows one such load covers
     constexpr int LPR = kChunks<D>;       // lanes (= 16-byte chunks) per row
     constexpr int RB = kAttnRowBytes<D>;
+    constexpr int TPB = BLK / kAttnTileKeys;          // 64-key tiles per key block: 1, 2 or 4
+    constexpr int QS = BLK > 128 ? BLK / 128 : 1;     // workgroups per (head, q-block), 128 queries each
 
-    const int x = blockIdx.x & 7, k = blockIdx.x >> 3;
+    const int x = blockIdx.x & 7, k0 = blockIdx.x >> 3;
+    const int sub = k0 % QS, k = k0 / QS;             // which 128 queries of the q-block
     const int s = (k / g) * 8 + x, hg = k % g;
     if (s >= m_total * hkv) return;
     // KV head outermost: the rows of one KV head run together, so the K/V of one head (not of all
@@ -196,6 +203,10 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     const int tid = threadIdx.x, l = tid & 63, half = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, held in a scalar register
     const int q_local = 32 * w + (l & 31);
+    const int qoff = 128 * sub;                               // the workgroup's first query within the q-block
+    const int q_len = bi.q_len - qoff < 128 ? bi.q_len - qoff : 128;   // its valid queries
+    if (q_len <= 0) return;                                   // a ragged q-block that ends before this part
+    const int q_tok0 = bi.q_tok0 + qoff;
 
     // The first two list entries are fetched together with the count (the memory is there whatever
     // the count says), so that the first tile loads do not wait for a second round trip.
@@ -210,20 +221,30 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     }
     b0 = b0 < 0 ? 0 : (b0 > I ? I : b0);
     b1 = b1 < 0 ? 0 : (b1 > I ? I : b1);
-    const int ntiles = 2 * nb;
+    // Tiles: TPB per listed block.  Of the diagonal block (only the last entry can be it) this part
+    // of the q-block needs the tiles up to its own last query, 2 (sub + 1) of them; that is fewer than
+    // TPB only for the first half of a 256-query block.  An odd count (64-key blocks) is made even
+    // with one more pass over the last tile with every key masked, so that the two register sets of
+    // the pipeline below keep alternating.
+    int nt_real = TPB * nb;
+    if (TPB > 2 && nb > 0 && 2 * (sub + 1) < TPB) {
+        const int bl = SPARSE ? list[nb - 1] : nb - 1;
+        if (bl >= I) nt_real -= TPB - 2 * (sub + 1);
+    }
+    const int ntiles = (nt_real + 1) & ~1;
 
     if (ntiles == 0) {   // empty list: O = 0, lse = -inf (uniform exit, before any barrier)
-        if (q_local < bi.q_len) {
-            uint16_t *op = O + ((size_t)(bi.q_tok0 + q_local) * hq + h) * D + (D / 2) * half;
+        if (q_local < q_len) {
+            uint16_t *op = O + ((size_t)(q_tok0 + q_local) * hq + h) * D + (D / 2) * half;
             const u32x4 z = {0u, 0u, 0u, 0u};
 #pragma unroll
             for (int i = 0; i < D / 16; ++i) *reinterpret_cast<u32x4 *>(op + 8 * i) = z;
-            if (lse != nullptr && half == 0) lse[(size_t)h * T + bi.q_tok0 + q_local] = -INFINITY;
+            if (lse != nullptr && half == 0) lse[(size_t)h * T + q_tok0 + q_local] = -INFINITY;
         }
         return;
     }
 
-#define FP_TILE_BLOCK(t) attn_tile_block<SPARSE>(list, (t), I)
+#define FP_TILE_BLOCK(t) attn_tile_block<SPARSE, TPB>(list, (t), I, nb)
 
     // Q^T B-fragments: query 32w + l%32, dims 16ks + 8*half..+7.  The loads are written as
     // assembly so that their completion is counted here and not by the compiler, which cannot see
@@ -231,8 +252,8 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     // with the exact count, for the fragments and the first K tile together.
     bf16x8 qb[KS];
     {
-        int row = q_local < bi.q_len ? q_local : bi.q_len - 1;
-        const uint16_t *qp = Q + ((size_t)(bi.q_tok0 + row) * hq + h) * D + 8 * half;
+        int row = q_local < q_len ? q_local : q_len - 1;
+        const uint16_t *qp = Q + ((size_t)(q_tok0 + row) * hq + h) * D + 8 * half;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
             asm volatile("global_load_dwordx4 %0, %1, off offset:%2" : "=&v"(qb[ks]) : "v"(qp), "n"(32 * ks) : "memory");
@@ -260,7 +281,7 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     }
 #define FP_LOAD(FULL, Xb, col_, blk_, odd_, ldsoff_)                                                      \
     do {                                                                                                  \
-        const int tok0_ = seq_tok0 + (blk_) * kBlock + (odd_) * kAttnTileKeys;                            \
+        const int tok0_ = seq_tok0 + (blk_) * BLK + (odd_) * kAttnTileKeys;                               \
         const int base_tok_ = tok0_ < last_tok ? tok0_ : last_tok;                                        \
         const char *base_ = Xb + (size_t)base_tok_ * row_bytes;                                           \
         const uint32_t dst_ = lds_base + (ldsoff_) + 16 * w * RB;                                         \
@@ -284,12 +305,12 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
 #define FP_LOAD_FULL(Xb, col_, t, ldsoff_)                                                                \
     do {                                                                                                  \
         const int b_ = FP_TILE_BLOCK(t);                                                                  \
-        FP_LOAD(true, Xb, col_, (b_ < I ? b_ : I - 1), ((t) & 1), ldsoff_);                               \
+        FP_LOAD(true, Xb, col_, (b_ < I ? b_ : I - 1), ((t) % TPB), ldsoff_);                             \
     } while (0)
 #define FP_LOAD_SAFE(Xb, col_, t, ldsoff_)                                                                \
     do {                                                                                                  \
         const int ts_ = (t) < ntiles ? (t) : ntiles - 1;                                                  \
-        FP_LOAD(false, Xb, col_, FP_TILE_BLOCK(ts_), (ts_ & 1), ldsoff_);                                 \
+        FP_LOAD(false, Xb, col_, FP_TILE_BLOCK(ts_), (ts_ % TPB), ldsoff_);                               \
     } while (0)
 
     f32x16 acc[NDT];
@@ -317,20 +338,28 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     // Causal limit of tile t for this lane: on the diagonal block, key kk of the tile is in the
     // lane's future if kk > query - tile offset (and keys past a ragged end lie beyond every stored
     // query); elsewhere nothing is masked.
-#define FP_LIM(t) (FP_TILE_BLOCK(t) == I ? q_local - ((t) & 1) * kAttnTileKeys - 4 * half : 2 * kAttnTileKeys)
+#define FP_LIM(t)                                                                                         \
+    ((TPB == 1 && (t) >= nt_real) ? -1                                                                    \
+     : (FP_TILE_BLOCK(t) == I ? qoff + q_local - ((t) % TPB) * kAttnTileKeys - 4 * half : 2 * kAttnTileKeys))
 
     // Prologue: S^T of tile 0 with its row max; on leaving it K[1] and V[0] are in, K[2] on its way.
     FP_LOAD(false, Kb, ld_kcol, b0, 0, FP_KBUF(0));
     FP_LOAD(false, Vb, ld_vcol, b0, 0, FP_VBUF(0));
-    FP_LOAD(false, Kb, ld_kcol, b0, 1, FP_KBUF(1));   // ntiles >= 2
-    FP_LOAD(false, Kb, ld_kcol, (nb > 1 ? b1 : b0), (nb > 1 ? 0 : 1), FP_KBUF(2));
+    if (TPB == 1) {   // tile t is list entry t (ntiles >= 2: with one entry, tile 1 is the masked repeat)
+        FP_LOAD(false, Kb, ld_kcol, (nb > 1 ? b1 : b0), 0, FP_KBUF(1));
+        FP_LOAD_SAFE(Kb, ld_kcol, 2, FP_KBUF(2));
+    } else {
+        FP_LOAD(false, Kb, ld_kcol, b0, 1, FP_KBUF(1));   // ntiles >= 2
+        if (TPB == 2) FP_LOAD(false, Kb, ld_kcol, (nb > 1 ? b1 : b0), (nb > 1 ? 0 : 1), FP_KBUF(2));
+        else FP_LOAD(false, Kb, ld_kcol, b0, 2, FP_KBUF(2));
+    }
     FP_WAIT_VMCNT(3 * LPT);   // Q and K[0] are in; V[0], K[1] and K[2] keep landing under the first QK^T
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qb[ks]));   // uses of Q stay behind the wait
     __syncthreads();
     f32x16 sA0, sA1, sB0, sB1;
     attn_qk<D>(smem, FP_KBUF(0) + k_frag, qb, sA0, sA1);
-    attn_mask(sA0, sA1, b0 == I ? q_local - 4 * half : 2 * kAttnTileKeys);
+    attn_mask(sA0, sA1, b0 == I ? qoff + q_local - 4 * half : 2 * kAttnTileKeys);
     m_run = attn_rowmax(sA0, sA1);   // finite: key 0 of tile 0 is visible to every query
     FP_WAIT_VMCNT(LPT);
     __syncthreads();
@@ -380,7 +409,7 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     // and a row only meets it as its diagonal); the list is ascending, so only its last block can
     // be the diagonal one.  A MAIN step t needs tiles t .. t+3 before it.  ntiles is even, and so
     // is the number of MAIN steps, so the register roles of the two S^T tiles alternate evenly.
-    const int n_plain = FP_TILE_BLOCK(ntiles - 1) == I ? ntiles - 2 : ntiles;
+    const int n_plain = FP_TILE_BLOCK(nt_real - 1) == I ? TPB * (nb - 1) : nt_real;
     const int t_main = (n_plain - 3) & ~1;   // negative: none
     int t = 0;
     for (; t < t_main; t += 2) {
@@ -422,12 +451,12 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
         for (int i = 0; i < 32 / RPL; ++i) {
             const int orow = RPL * i + l / LPR;
             const u32x4 v = *reinterpret_cast<const u32x4 *>(ob + orow * RB + (pc << 4));
-            if (32 * w + orow < bi.q_len)
-                *reinterpret_cast<u32x4 *>(O + ((size_t)(bi.q_tok0 + 32 * w + orow) * hq + h) * D + ((pc ^ (orow & kSwz<D>)) << 3)) = v;
+            if (32 * w + orow < q_len)
+                *reinterpret_cast<u32x4 *>(O + ((size_t)(q_tok0 + 32 * w + orow) * hq + h) * D + ((pc ^ (orow & kSwz<D>)) << 3)) = v;
         }
     }
-    if (q_local < bi.q_len && lse != nullptr && half == 0)
-        lse[(size_t)h * T + bi.q_tok0 + q_local] = l_tot > 0.f ? m_run * c + __log2f(l_tot) : -INFINITY;
+    if (q_local < q_len && lse != nullptr && half == 0)
+        lse[(size_t)h * T + q_tok0 + q_local] = l_tot > 0.f ? m_run * c + __log2f(l_tot) : -INFINITY;
 #undef FP_TILE_BLOCK
 #undef FP_LOAD
 #undef FP_LOAD_FULL

@@ -14,7 +14,6 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
-constexpr int kBlock = 128;    // tokens per block (Appendix A)
 // The kernels are templates over the head dimension D (64, 128 or 256).  A row of D bf16 is
 // D/8 16-byte chunks; LDS tiles are unpadded and keep chunk c of row r at position c ^ (r & kSwz<D>)
 // (see the kernels), where the mask is the row's chunk count minus one, capped at 15.

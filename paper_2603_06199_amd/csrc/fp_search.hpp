@@ -98,11 +98,16 @@ __global__ __launch_bounds__(256) void pool_k_kernel(const uint16_t *__restrict_
 template <int D> constexpr int kSearchPlane = 32 * 2 * D;           // one plane (hi or lo) of a 32-row tile, unpadded
 template <int D> constexpr int kSearchTile = 2 * kSearchPlane<D>;   // hi + lo
 constexpr int kSearchBufs = 2;
-constexpr int kSearchHeads = 2;                        // query heads per workgroup
-constexpr int kSearchMailbox = 2 * kSearchHeads * 32 * 8;   // [step parity][head][pooled key] (max, sum)
-template <int D> constexpr int kSearchStageBytes = kSearchBufs * kSearchTile<D> + kSearchMailbox;
+// A q-block of BLK queries of one head takes BLK/64 waves (64 queries each); the workgroup's four
+// waves serve 4/(BLK/64) query heads of one KV group: 4 at block 64, 2 at 128, 1 at 256.
+template <int BLK> constexpr int kSearchWavesPerHead = BLK / 64;
+template <int BLK> constexpr int kSearchHeads = 4 / kSearchWavesPerHead<BLK>;
+// [step parity][head][posting wave][pooled key] (max, sum): every wave of a head but its first posts
+template <int BLK> constexpr int kSearchMailbox =
+    2 * kSearchHeads<BLK> * (kSearchWavesPerHead<BLK> > 1 ? kSearchWavesPerHead<BLK> - 1 : 1) * 32 * 8;
+template <int D, int BLK> constexpr int kSearchStageBytes = kSearchBufs * kSearchTile<D> + kSearchMailbox<BLK>;
 constexpr int kSearchRowHeader = 64;                   // per-head row maxima and prologue exchange, ahead of the rows
-constexpr int kSearchCandBytes = kSearchHeads * (32 + 4) * 4;   // SELECT: candidate tile indices + count per head
+constexpr int kSearchCandBytes = 4 * (32 + 4) * 4;     // SELECT: candidate tile indices + count per head
 constexpr float kSearchSafeLogit = 100.f;              // |x| below this: 2^x needs no reference point in fp32
 constexpr float kSearchEpsNoop = 0x1p-26f;             // eps below this cannot change an fp32 row total >= 1
 constexpr int kSearchExactTiles = 4;                   // SELECT: rows of up to this many tiles run both planes throughout
@@ -213,7 +218,7 @@ struct SelectArgs {
     int32_t *idx, *cnt;
 };
 
-template <int D, bool SELECT>
+template <int D, int BLK, bool SELECT>
 __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ kb_hi, const uint16_t *__restrict__ kb_lo,
     const float2 *__restrict__ kb_norm, const RowRec *__restrict__ rows_ranked, const int32_t *__restrict__ order,
@@ -224,8 +229,11 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
     constexpr int LPW = D / 32;           // wave-wide 1 KB loads per wave and tile (both planes: 4 waves x LPW)
     constexpr int RPL = kRowsPerLoad<D>;  // pooled-key rows one such load covers
     constexpr int LPR = kChunks<D>;       // lanes per row
+    constexpr int WPH = kSearchWavesPerHead<BLK>;   // waves per query head
+    constexpr int HPW = kSearchHeads<BLK>;          // query heads per workgroup
+    constexpr int NPOST = WPH > 1 ? WPH - 1 : 1;    // mailbox slots per head and pooled key
     float2 *mbox = reinterpret_cast<float2 *>(smem + kSearchBufs * kSearchTile<D>);
-    float *mtop = reinterpret_cast<float *>(smem + kSearchStageBytes<D>);   // [head] max of the row's pair maxima
+    float *mtop = reinterpret_cast<float *>(smem + kSearchStageBytes<D, BLK>);   // [head] max of the row's pair maxima
     float *xchg = mtop + 4;                                              // [wave] prologue exchange: query norm, key norm
     float *ms_all = mtop + kSearchRowHeader / sizeof(float);
 
@@ -238,8 +246,8 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
     const int I = bi.I;
     const int tid = threadIdx.x, l = tid & 63, half = l >> 5;
     const int w = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave index, held in a scalar register
-    const int hd = w >> 1, qh = w & 1;
-    const int hg = ch * kSearchHeads + hd;
+    const int hd = w / WPH, qh = w % WPH;   // head within the workgroup, 64-query part within the head
+    const int hg = ch * HPW + hd;
     const bool active = hg < g;
     const int h = hk * g + (active ? hg : g - 1);
     float *ms = ms_all + (size_t)hd * n_pad;   // the row: t_J = m_J + log2 S_J per block pair
@@ -266,8 +274,9 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
     // (J > I) are clamped to I: they are computed and dropped.  A row that runs on the hi plane
     // alone does not load the other one (waves 2 and 3 then issue nothing).
     const int ntile = I / 32 + 1;
-    const bool ragged = bi.q_len < kBlock;
-    const bool hi_only = SELECT && !ragged && ntile > kSearchExactTiles && sel.alpha > 0.f;
+    const bool ragged = bi.q_len < BLK;
+    // the hi-plane pass and its re-scoring are laid out for two waves per head (block 128)
+    const bool hi_only = SELECT && BLK == 128 && !ragged && ntile > kSearchExactTiles && sel.alpha > 0.f;
     const uint32_t lds_base = (uint32_t)(uintptr_t)(FP_LDS(char) *)smem;
     const uint32_t row_bytes = (uint32_t)hkv * D * 2;
     const size_t pl_off = ((size_t)bi.kb_row0 * hkv + hk) * D * 2;
@@ -314,7 +323,10 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
     }
     __syncthreads();
     // wave-uniform values, moved to scalar registers so that the branches on them are scalar too
-    const float qnorm = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(fmaxf(xchg[4 * hd], xchg[4 * hd + 2]))));   // the head's 128 queries
+    float qn_head = xchg[2 * (hd * WPH)];
+#pragma unroll
+    for (int i = 1; i < WPH; ++i) qn_head = fmaxf(qn_head, xchg[2 * (hd * WPH + i)]);
+    const float qnorm = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(qn_head)));   // all queries of the head's q-block
     kmax = __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(fmaxf(fmaxf(xchg[1], xchg[3]), fmaxf(xchg[5], xchg[7])))));
     // small: no logit of this row can leave (-100, 100), and eps is a rounding no-op
     const bool small = !ragged && qnorm * kmax * 1.01f < kSearchSafeLogit && eps <= kSearchEpsNoop;
@@ -325,12 +337,19 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
     // its own pair from the previous step and files the result; wait for tile jt+1.
     float2 prev = make_float2(-INFINITY, 0.f);
     float m_top = -INFINITY;
-#define FP_FILE(SMALL, Jp_, post_)                                                                        \
+    // slot of (step parity, posting wave qh >= 1) for this head and lane
+#define FP_MBOX(par_, qh_) mbox[(((par_) * HPW + hd) * NPOST + ((qh_) - 1)) * 32 + l]
+#define FP_FILE(SMALL, Jp_, par_)                                                                         \
     do {                                                                                                  \
+        float2 mg_ = prev;                                                                                \
+        _Pragma("unroll") for (int p_ = 1; p_ < WPH; ++p_) {                                              \
+            const float2 post_ = FP_MBOX(par_, p_);                                                       \
+            if (SMALL) mg_.y += post_.y;                                                                  \
+            else mg_ = search_merge(mg_, post_);                                                          \
+        }                                                                                                 \
         if (SMALL) {                                                                                      \
-            ms[Jp_] = __log2f(prev.y + (post_).y);                                                        \
+            ms[Jp_] = __log2f(mg_.y);                                                                     \
         } else {                                                                                          \
-            const float2 mg_ = search_merge(prev, (post_));                                               \
             ms[Jp_] = mg_.x + __log2f(mg_.y);                                                             \
             m_top = fmaxf(m_top, mg_.x);                                                                  \
         }                                                                                                 \
@@ -345,10 +364,10 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
             const float2 v_ = SMALL ? search_reduce_small(acc_) : search_reduce<RAGGED>(acc_, bi.q_len, 64 * qh, half); \
             if (l < 32) {                                                                                 \
                 if (qh) {                                                                                 \
-                    mbox[((jt_ & 1) * kSearchHeads + hd) * 32 + l] = v_;                                  \
+                    FP_MBOX(jt_ & 1, qh) = v_;                                                            \
                 } else {                                                                                  \
                     const int Jp_ = 32 * (jt_ - 1) + l;                                                   \
-                    if (jt_ > 0 && Jp_ <= I) FP_FILE(SMALL, Jp_, mbox[(((jt_ - 1) & 1) * kSearchHeads + hd) * 32 + l]); \
+                    if (jt_ > 0 && Jp_ <= I) FP_FILE(SMALL, Jp_, (jt_ - 1) & 1);                          \
                     prev = v_;                                                                            \
                 }                                                                                         \
             }                                                                                             \
@@ -375,7 +394,7 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
     // more so that both waves of a head see the complete row
     if (active && qh == 0) {
         const int Jp = 32 * (ntile - 1) + l;
-        if (l < 32 && Jp <= I) FP_FILE(small, Jp, mbox[(((ntile - 1) & 1) * kSearchHeads + hd) * 32 + l]);
+        if (l < 32 && Jp <= I) FP_FILE(small, Jp, (ntile - 1) & 1);
         m_top = wave_max(m_top);
         if (l == 0) mtop[hd] = m_top;
     }
@@ -394,7 +413,7 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
     // ------------------------------------------------------------------------------------------
     float T_exact = -INFINITY;   // scanning wave: max of the re-scored t_J
     if (SELECT && hi_only) {
-        int32_t *cand = reinterpret_cast<int32_t *>(ms_all + (size_t)kSearchHeads * n_pad) + hd * 36;   // [32] indices, [32] = count
+        int32_t *cand = reinterpret_cast<int32_t *>(ms_all + (size_t)HPW * n_pad) + hd * 36;   // [32] indices, [32] = count
         const float la = __log2f(sel.alpha);
         float lo_t = -INFINITY, hi_t = -INFINITY;
         // eps_J = qn |lo_J| + slack; the slack stands for the fp32 accumulation noise of the two
@@ -466,7 +485,7 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
                 if (l == 0) cand[32] = have;
             }
             __syncthreads();
-            const int32_t *cand0 = reinterpret_cast<int32_t *>(ms_all + (size_t)kSearchHeads * n_pad);
+            const int32_t *cand0 = reinterpret_cast<int32_t *>(ms_all + (size_t)HPW * n_pad);
             const int n0 = cand0[32], n1 = cand0[36 + 32];
             if (n0 == 0 && n1 == 0) break;
             const int nmine = hd ? n1 : n0;
@@ -511,6 +530,7 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
 #undef FP_LOAD_TILE
 #undef FP_BUF
 #undef FP_FILE
+#undef FP_MBOX
     if (!active) return;
     if (SELECT && qh) return;   // the list is compacted by one wave per head
     // Eq. 3-4.  With M the max of the row's pair maxima, S'_J = S_J 2^(m_J - M) and the score is
@@ -528,9 +548,9 @@ __global__ __launch_bounds__(256, D > 128 ? 2 : (SELECT ? 3 : 4)) void search_ke
     for (int J = l; J <= I; J += 64) tot += fast_exp2(ms[J] - Tm);
     tot = wave_sum(tot);
     const float denom = tot + (small ? 0.f : eps * fast_exp2(mtop[hd] - Tm));
-    if (!SELECT) {   // each wave writes half of the sequence's columns; columns past its last key block are left alone
+    if (!SELECT) {   // the head's waves share the sequence's columns; columns past its last key block are left alone
         float *out = scores + ((size_t)h * m_total + r) * n_max;
-        for (int J = l + 64 * qh; J < bi.n_kb; J += 128) out[J] = J <= I ? fast_exp2(ms[J] - Tm) / denom : 0.f;
+        for (int J = l + 64 * qh; J < bi.n_kb; J += 64 * WPH) out[J] = J <= I ? fast_exp2(ms[J] - Tm) / denom : 0.f;
         return;
     }
     // Fused Alg. 2: the normalised scores (the same fp32 expression as above) replace the row in

@@ -264,13 +264,13 @@ def layout(cu_seqlens: Sequence[int], block: int = BLOCK):
 
 
 def forced_density_lists(cu_seqlens: Sequence[int], hq: int, density: float, seed: int,
-                         sink_blocks: int = 2, window_blocks: int = 4):
+                         sink_blocks: int = 2, window_blocks: int = 4, block: int = BLOCK):
     """Random causal block lists with a target kept fraction; sink and window blocks always kept.
 
     Returns (idx[hq, m_total, n_max] int32, cnt[hq, m_total] int32); ``idx`` rows are ascending
     and entries past ``cnt`` are left at -1.
     """
-    m_total, n_max, row_offset = layout(cu_seqlens)
+    m_total, n_max, row_offset = layout(cu_seqlens, block)
     idx = np.full((hq, m_total, n_max), -1, np.int32)
     cnt = np.zeros((hq, m_total), np.int32)
     g = np.random.default_rng(seed)

@@ -47,9 +47,9 @@ def own_columns_mask(cu, block=128):
     return mask
 
 
-def compare_scores(P_gpu, P_ref, cu, rows=None):
-    mask = causal_mask(cu)
-    own = own_columns_mask(cu)
+def compare_scores(P_gpu, P_ref, cu, rows=None, block=128):
+    mask = causal_mask(cu, block)
+    own = own_columns_mask(cu, block)
     if rows is not None:
         sel = np.zeros(mask.shape[0], bool); sel[list(rows)] = True
         mask &= sel[:, None]
@@ -75,12 +75,12 @@ def lists_to_mask(idx, cnt):
     return out[:, :, :n]
 
 
-def compare_lists_banded(idx_g, cnt_g, P_ref, cu, alpha, sink_tokens=256, window_tokens=512, rows=None):
+def compare_lists_banded(idx_g, cnt_g, P_ref, cu, alpha, sink_tokens=256, window_tokens=512, rows=None, block=128):
     """Lists from GPU scores vs lists from oracle scores: equal except for pairs whose oracle
     score lies within BAND (relative) of the threshold.  Returns (#mismatching pairs, #pairs in band)."""
-    idx_r, cnt_r = oracle.threshold(P_ref, cu, alpha, sink_tokens=sink_tokens, window_tokens=window_tokens)
+    idx_r, cnt_r = oracle.threshold(P_ref, cu, alpha, block=block, sink_tokens=sink_tokens, window_tokens=window_tokens)
     mg, mr = lists_to_mask(idx_g, cnt_g), lists_to_mask(idx_r, cnt_r)
-    cm = causal_mask(cu)
+    cm = causal_mask(cu, block)
     if rows is not None:
         sel = np.zeros(cm.shape[0], bool); sel[list(rows)] = True
         cm &= sel[:, None]

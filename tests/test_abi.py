@@ -53,7 +53,8 @@ def test_layout_matches_block_arithmetic(lib):
     ([0, 128], 0, 1, 128, 128, 0.0, B.FP_ERR_INVALID_ARG),
     ([0, 128], 8, 2, 128, 128, float("nan"), B.FP_ERR_INVALID_ARG),
     ([0, 128], 8, 2, 96, 128, 0.0, B.FP_ERR_UNSUPPORTED),      # head_dim other than 64, 128, 256
-    ([0, 128], 8, 2, 128, 64, 0.0, B.FP_ERR_UNSUPPORTED),      # block
+    ([0, 128], 8, 2, 128, 32, 0.0, B.FP_ERR_UNSUPPORTED),      # block other than 64, 128, 256
+    ([0, 128], 8, 2, 64, 256, 0.0, B.FP_ERR_UNSUPPORTED),      # blocks other than 128 need head_dim 128
     ([0, 4097 * 128], 8, 2, 128, 128, 0.0, B.FP_ERR_UNSUPPORTED),  # more than 4096 blocks in a sequence
 ])
 def test_bad_shapes_are_rejected_on_the_host(lib, cu, hq, hkv, d, blk, scale, code):
