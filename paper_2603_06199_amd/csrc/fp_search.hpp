@@ -606,11 +606,11 @@ __global__ __launch_bounds__(256) void threshold_kernel(const float *__restrict_
 
     float mx = -INFINITY;
     if (VEC) {
-        // 16 bytes per lane and four loads in flight per wave; the last vector may reach up to three
+        // 16 bytes per lane and up to eight loads in flight per wave; the last vector may reach up to three
         // entries past the diagonal (still inside the row), which are left out of the max.
         const float4 *row4 = reinterpret_cast<const float4 *>(row);
         float4 *buf4 = reinterpret_cast<float4 *>(buf);
-#pragma unroll 4
+#pragma unroll 8
         for (int j4 = l; 4 * j4 <= I; j4 += 64) {
             const float4 v = row4[j4];
             buf4[j4] = v;
