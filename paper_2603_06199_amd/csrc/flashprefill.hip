@@ -95,9 +95,6 @@ int search_stage_bytes(int head_dim, int block) {
     return block == 64 ? fp::kSearchStageBytes<128, 64> : block == 128 ? fp::kSearchStageBytes<128, 128> : fp::kSearchStageBytes<128, 256>;
 }
 int search_heads_per_wg(int block) { return block == 64 ? 4 : block == 128 ? 2 : 1; }
-int attn_lds_bytes(int head_dim) {
-    return head_dim == 64 ? fp::kAttnLds<64> : head_dim == 128 ? fp::kAttnLds<128> : fp::kAttnLds<256>;
-}
 
 template <int D, int BLK>
 bool set_lds_ceilings() {
@@ -108,9 +105,9 @@ bool set_lds_ceilings() {
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::search_kernel<D, BLK, true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, search_lds_max) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<D, BLK, true>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds<D>) == hipSuccess;
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds<D, BLK>) == hipSuccess;
     ok = ok && hipFuncSetAttribute(reinterpret_cast<const void *>(fp::attn_kernel<D, BLK, false>),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds<D>) == hipSuccess;
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, fp::kAttnLds<D, BLK>) == hipSuccess;
     return ok;
 }
 
@@ -438,10 +435,10 @@ static fp_status launch_attn_d(fp_plan *p, bool sparse, const void *Q, const voi
                    *v = static_cast<const uint16_t *>(V);
     uint16_t *o = static_cast<uint16_t *>(O);
     if (sparse)
-        fp::attn_kernel<D, BLK, true><<<dim3(grid), 256, fp::kAttnLds<D>, st>>>(q, k, v, idx, cnt, p->d_rows_ranked, p->d_order, p->m_total,
+        fp::attn_kernel<D, BLK, true><<<dim3(grid), 64 * fp::kAttnWaves<BLK>, fp::kAttnLds<D, BLK>, st>>>(q, k, v, idx, cnt, p->d_rows_ranked, p->d_order, p->m_total,
                                                                           p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     else
-        fp::attn_kernel<D, BLK, false><<<dim3(grid), 256, fp::kAttnLds<D>, st>>>(q, k, v, nullptr, nullptr, p->d_rows_ranked, p->d_order,
+        fp::attn_kernel<D, BLK, false><<<dim3(grid), 64 * fp::kAttnWaves<BLK>, fp::kAttnLds<D, BLK>, st>>>(q, k, v, nullptr, nullptr, p->d_rows_ranked, p->d_order,
                                                                            p->m_total, p->n_max, p->hq, p->hkv, p->g, p->T, p->c, o, lse);
     return launch_status();
 }

@@ -15,12 +15,16 @@ namespace fp {
 //     lane group then hit four different 64-byte bank groups.
 // Head dimension 128: 16 KB tiles, 80 KB, two workgroups per CU.  64: 40 KB.  256: 32 KB tiles,
 // all 160 KB of a CU, one workgroup (its accumulators and query fragments need 512 registers).
-constexpr int kAttnTileKeys = 64;
+// A workgroup has one wave per 32 queries of its q-block part, four at most; a 64-query block gets
+// two waves and 32-key tiles (40 KB, four workgroups per CU), so that every wave still loads 16
+// rows of each tile and no wave repeats another's queries.
+template <int BLK> constexpr int kAttnWaves = BLK < 128 ? BLK / 32 : 4;
+template <int BLK> constexpr int kAttnTileKeys = 16 * kAttnWaves<BLK>;
 template <int D> constexpr int kAttnRowBytes = 2 * D;
-template <int D> constexpr int kAttnTile = kAttnTileKeys * kAttnRowBytes<D>;   // 16384 at D = 128
+template <int D, int KT> constexpr int kAttnTile = KT * kAttnRowBytes<D>;   // 16384 at D = 128, 64 keys
 constexpr int kAttnKBufs = 3, kAttnVBufs = 2;
-template <int D> constexpr int kAttnVBase = kAttnKBufs * kAttnTile<D>;
-template <int D> constexpr int kAttnLds = (kAttnKBufs + kAttnVBufs) * kAttnTile<D>;   // 81920 at D = 128
+template <int D, int KT> constexpr int kAttnVBase = kAttnKBufs * kAttnTile<D, KT>;
+template <int D, int BLK> constexpr int kAttnLds = (kAttnKBufs + kAttnVBufs) * kAttnTile<D, kAttnTileKeys<BLK>>;   // 81920 at D = 128
 template <int D> constexpr int kAttnVSwz = (D / 32 - 1 < 3 ? D / 32 - 1 : 3);     // V rows: chunk ^ 4 (r & kAttnVSwz)
 
 // ds_read_b64_tr_b16: within each group of 16 lanes the 16 x 4 b16 values addressed by the
@@ -36,6 +40,9 @@ __device__ __forceinline__ s16x4 lds_read_tr(const char *p) {
  * One workgroup (4 waves) per (query head, q-block row); wave w owns queries 32w..32w+31 of the
  * block.  Alg. 3's loop over the listed blocks runs as a loop over 64-key tiles (two per block)
  * whose addresses come straight from the index list: an unlisted block costs no instruction.
+ * (Other block sizes: a 256-query block is two such workgroups over four tiles per block, a
+ * 64-query block one workgroup of two waves over two 32-key tiles per block; the counts below are
+ * for 64-key tiles.)
  *
  * Per tile and wave:
  *   S^T = K Q^T  (keys x queries, 16 MFMA 32x32x16): the query index is the lane column, so the
@@ -62,7 +69,7 @@ __device__ __forceinline__ s16x4 lds_read_tr(const char *p) {
  * head, so one head's K and V (128 MiB each at 512K tokens) are what the last-level cache holds
  * at a time, not every head's.
  */
-// Block of 64-key tile t: entry t / TPB of the list (TPB tiles per block), the entry index kept
+// Block of key tile t: entry t / TPB of the list (TPB tiles per block), the entry index kept
 // below nb and the block id inside [0, I].
 template <bool SPARSE, int TPB>
 __device__ __forceinline__ int attn_tile_block(const int32_t *list, int t, int I, int nb) {
@@ -73,35 +80,45 @@ __device__ __forceinline__ int attn_tile_block(const int32_t *list, int t, int I
     return b < 0 ? 0 : (b > I ? I : b);
 }
 
-// S^T (64 keys x 32 queries) of one K tile: s0 = keys 0..31, s1 = keys 32..63.
+// S^T (KT keys x 32 queries) of one K tile: s0 = keys 0..31, s1 = keys 32..63 (untouched for a 32-key tile).
 // kaddr = buffer base + the lane's row and swizzled chunk for k-slice 0; slice ks sits at kaddr ^ (ks << 5).
-template <int D>
+template <int D, int KT>
 __device__ __forceinline__ void attn_qk(const char *smem, uint32_t kaddr, const bf16x8 (&qb)[D / 16], f32x16 &s0, f32x16 &s1) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { s0[i] = 0.f; s1[i] = 0.f; }
+    for (int i = 0; i < 16; ++i) { s0[i] = 0.f; if (KT > 32) s1[i] = 0.f; }
 #pragma unroll
     for (int ks = 0; ks < D / 16; ++ks) {
         const char *kp = smem + (kaddr ^ (uint32_t)(ks << 5));
         const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(kp);
-        const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(kp + 32 * kAttnRowBytes<D>);
         s0 = mfma32(a0, qb[ks], s0);
-        s1 = mfma32(a1, qb[ks], s1);
+        if (KT > 32) {
+            const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(kp + 32 * kAttnRowBytes<D>);
+            s1 = mfma32(a1, qb[ks], s1);
+        }
     }
 }
 
 // Causal mask of a diagonal tile: key 8(i/4) + i%4 (+32 for s1) is in this lane's future if it
 // exceeds lim = query - tile offset - 4*half.
+template <int KT>
 __device__ __forceinline__ void attn_mask(f32x16 &s0, f32x16 &s1, int lim) {
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int kk = 8 * (i >> 2) + (i & 3);
         if (kk > lim) s0[i] = -INFINITY;
-        if (kk + 32 > lim) s1[i] = -INFINITY;
+        if (KT > 32 && kk + 32 > lim) s1[i] = -INFINITY;
     }
 }
 
-// Row max of one tile's S^T: 32 of the 64 keys are in this lane, the rest in lane^32.
+// Row max of one tile's S^T: half of the tile's keys are in this lane, the rest in lane^32.
+template <int KT>
 __device__ __forceinline__ float attn_rowmax(const f32x16 &s0, const f32x16 &s1) {
+    if (KT == 32) {
+        float ta = max3(s0[0], s0[1], s0[2]);
+#pragma unroll
+        for (int i = 3; i < 15; i += 2) ta = max3(ta, s0[i], s0[i + 1]);
+        return halves_max(fmaxf(ta, s0[15]));
+    }
     float ta = max3(s0[0], s0[1], s0[2]), tb = max3(s1[0], s1[1], s1[2]);
 #pragma unroll
     for (int i = 3; i < 15; i += 2) {
@@ -136,28 +153,31 @@ __device__ __forceinline__ void attn_new_max(float tm, float c, float &m_run, fl
 
 // p = 2^(c*s - c*m), rounded to bf16 and laid out as the B operand of the PV product; the row sum
 // is taken over the fp32 values before rounding, so lse does not inherit bf16's 2^-9 rounding.
+template <int KT>
 __device__ __forceinline__ void attn_exp(const f32x16 &s0, const f32x16 &s1, float c, float mc, float &l_run,
                                          bf16x8 (&pb)[2][2]) {
     float la = 0.f, lb = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const float pa = fast_exp2(__builtin_fmaf(s0[i], c, -mc));
-        const float pq = fast_exp2(__builtin_fmaf(s1[i], c, -mc));
         la += pa;
-        lb += pq;
         pb[0][i >> 3][i & 7] = (__bf16)pa;
-        pb[1][i >> 3][i & 7] = (__bf16)pq;
+        if (KT > 32) {
+            const float pq = fast_exp2(__builtin_fmaf(s1[i], c, -mc));
+            lb += pq;
+            pb[1][i >> 3][i & 7] = (__bf16)pq;
+        }
     }
     l_run += la + lb;
 }
 
-// O^T += V^T P^T for one 64-key tile: V^T fragments by transpose reads of the row-major V tile.
+// O^T += V^T P^T for one KT-key tile: V^T fragments by transpose reads of the row-major V tile.
 // vaddr[dt] = buffer base + the lane's row/column offsets with the swizzle of d-tile dt folded in.
-template <int D>
+template <int D, int KT>
 __device__ __forceinline__ void attn_pv(const char *smem, const uint32_t (&vaddr)[D / 32], const bf16x8 (&pb)[2][2],
                                         f32x16 (&acc)[D / 32]) {
 #pragma unroll
-    for (int kt2 = 0; kt2 < 2; ++kt2)
+    for (int kt2 = 0; kt2 < KT / 32; ++kt2)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
@@ -171,7 +191,7 @@ __device__ __forceinline__ void attn_pv(const char *smem, const uint32_t (&vaddr
 }
 
 template <int D, int BLK, bool SPARSE>
-__global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
+__global__ __launch_bounds__(64 * kAttnWaves<BLK>, D > 128 ? 1 : 2) void attn_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int32_t *__restrict__ idx, const int32_t *__restrict__ cnt, const RowRec *__restrict__ rows_ranked,
     const int32_t *__restrict__ order, int m_total, int n_max, int hq, int hkv, int g, int T, float c,
@@ -179,12 +199,14 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     extern __shared__ __attribute__((aligned(16))) char smem[];
     constexpr int KS = D / 16;            // k-slices of the QK^T contraction
     constexpr int NDT = D / 32;           // 32-wide tiles of the head dimension in the output
-    constexpr int LPT = D / 32;           // wave-wide 1 KB loads per wave and tile (64 rows over 4 waves)
+    constexpr int KT = kAttnTileKeys<BLK>;   // keys per tile: 64, or 32 for the two-wave workgroup of a 64-query block
+    constexpr int LPT = D / 32;           // wave-wide 1 KB loads per wave and tile (16 rows per wave)
     constexpr int RPL = kRowsPerLoad<D>;  // rows one such load covers
     constexpr int LPR = kChunks<D>;       // lanes (= 16-byte chunks) per row
     constexpr int RB = kAttnRowBytes<D>;
-    constexpr int TPB = BLK / kAttnTileKeys;          // 64-key tiles per key block: 1, 2 or 4
+    constexpr int TPB = BLK / KT;                     // key tiles per key block: 2 or 4
     constexpr int QS = BLK > 128 ? BLK / 128 : 1;     // workgroups per (head, q-block), 128 queries each
+    static_assert(TPB % 2 == 0, "the two register sets of the pipeline alternate over an even tile count");
 
     const int x = blockIdx.x & 7, k0 = blockIdx.x >> 3;
     const int sub = k0 % QS, k = k0 / QS;             // which 128 queries of the q-block
@@ -223,15 +245,12 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     b1 = b1 < 0 ? 0 : (b1 > I ? I : b1);
     // Tiles: TPB per listed block.  Of the diagonal block (only the last entry can be it) this part
     // of the q-block needs the tiles up to its own last query, 2 (sub + 1) of them; that is fewer than
-    // TPB only for the first half of a 256-query block.  An odd count (64-key blocks) is made even
-    // with one more pass over the last tile with every key masked, so that the two register sets of
-    // the pipeline below keep alternating.
-    int nt_real = TPB * nb;
+    // TPB only for the first half of a 256-query block.  The count is even in every case.
+    int ntiles = TPB * nb;
     if (TPB > 2 && nb > 0 && 2 * (sub + 1) < TPB) {
         const int bl = SPARSE ? list[nb - 1] : nb - 1;
-        if (bl >= I) nt_real -= TPB - 2 * (sub + 1);
+        if (bl >= I) ntiles -= TPB - 2 * (sub + 1);
     }
-    const int ntiles = (nt_real + 1) & ~1;
 
     if (ntiles == 0) {   // empty list: O = 0, lse = -inf (uniform exit, before any barrier)
         if (q_local < q_len) {
@@ -281,7 +300,7 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     }
 #define FP_LOAD(FULL, Xb, col_, blk_, odd_, ldsoff_)                                                      \
     do {                                                                                                  \
-        const int tok0_ = seq_tok0 + (blk_) * BLK + (odd_) * kAttnTileKeys;                               \
+        const int tok0_ = seq_tok0 + (blk_) * BLK + (odd_) * KT;                                          \
         const int base_tok_ = tok0_ < last_tok ? tok0_ : last_tok;                                        \
         const char *base_ = Xb + (size_t)base_tok_ * row_bytes;                                           \
         const uint32_t dst_ = lds_base + (ldsoff_) + 16 * w * RB;                                         \
@@ -296,8 +315,8 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
         }                                                                                                 \
     } while (0)
     // K tile t lives in K buffer t % 3, V tile t in V buffer t % 2.
-#define FP_KBUF(t) ((uint32_t)(((t) % kAttnKBufs) * kAttnTile<D>))
-#define FP_VBUF(t) ((uint32_t)(kAttnVBase<D> + ((t) & 1) * kAttnTile<D>))
+#define FP_KBUF(t) ((uint32_t)(((t) % kAttnKBufs) * kAttnTile<D, KT>))
+#define FP_VBUF(t) ((uint32_t)(kAttnVBase<D, KT> + ((t) & 1) * kAttnTile<D, KT>))
     // FULL loads are for tiles known to lie before the diagonal block, hence complete; the block id
     // is kept below I so that even a malformed (non-ascending) list cannot reach past the sequence.
     // Other loads clamp every row to the sequence's last token, and the tile index to the row's
@@ -338,29 +357,22 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     // Causal limit of tile t for this lane: on the diagonal block, key kk of the tile is in the
     // lane's future if kk > query - tile offset (and keys past a ragged end lie beyond every stored
     // query); elsewhere nothing is masked.
-#define FP_LIM(t)                                                                                         \
-    ((TPB == 1 && (t) >= nt_real) ? -1                                                                    \
-     : (FP_TILE_BLOCK(t) == I ? qoff + q_local - ((t) % TPB) * kAttnTileKeys - 4 * half : 2 * kAttnTileKeys))
+#define FP_LIM(t) (FP_TILE_BLOCK(t) == I ? qoff + q_local - ((t) % TPB) * KT - 4 * half : 2 * KT)
 
     // Prologue: S^T of tile 0 with its row max; on leaving it K[1] and V[0] are in, K[2] on its way.
     FP_LOAD(false, Kb, ld_kcol, b0, 0, FP_KBUF(0));
     FP_LOAD(false, Vb, ld_vcol, b0, 0, FP_VBUF(0));
-    if (TPB == 1) {   // tile t is list entry t (ntiles >= 2: with one entry, tile 1 is the masked repeat)
-        FP_LOAD(false, Kb, ld_kcol, (nb > 1 ? b1 : b0), 0, FP_KBUF(1));
-        FP_LOAD_SAFE(Kb, ld_kcol, 2, FP_KBUF(2));
-    } else {
-        FP_LOAD(false, Kb, ld_kcol, b0, 1, FP_KBUF(1));   // ntiles >= 2
-        if (TPB == 2) FP_LOAD(false, Kb, ld_kcol, (nb > 1 ? b1 : b0), (nb > 1 ? 0 : 1), FP_KBUF(2));
-        else FP_LOAD(false, Kb, ld_kcol, b0, 2, FP_KBUF(2));
-    }
+    FP_LOAD(false, Kb, ld_kcol, b0, 1, FP_KBUF(1));   // ntiles >= 2
+    if (TPB == 2) FP_LOAD(false, Kb, ld_kcol, (nb > 1 ? b1 : b0), (nb > 1 ? 0 : 1), FP_KBUF(2));
+    else FP_LOAD(false, Kb, ld_kcol, b0, 2, FP_KBUF(2));
     FP_WAIT_VMCNT(3 * LPT);   // Q and K[0] are in; V[0], K[1] and K[2] keep landing under the first QK^T
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qb[ks]));   // uses of Q stay behind the wait
     __syncthreads();
     f32x16 sA0, sA1, sB0, sB1;
-    attn_qk<D>(smem, FP_KBUF(0) + k_frag, qb, sA0, sA1);
-    attn_mask(sA0, sA1, b0 == I ? qoff + q_local - 4 * half : 2 * kAttnTileKeys);
-    m_run = attn_rowmax(sA0, sA1);   // finite: key 0 of tile 0 is visible to every query
+    attn_qk<D, KT>(smem, FP_KBUF(0) + k_frag, qb, sA0, sA1);
+    attn_mask<KT>(sA0, sA1, b0 == I ? qoff + q_local - 4 * half : 2 * KT);
+    m_run = attn_rowmax<KT>(sA0, sA1);   // finite: key 0 of tile 0 is visible to every query
     FP_WAIT_VMCNT(LPT);
     __syncthreads();
 
@@ -389,16 +401,16 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
             if (MODE == TAIL) FP_LOAD_SAFE(Kb, ld_kcol, t_ + 3, FP_KBUF(t_ + 3));                         \
         }                                                                                                 \
         bf16x8 pb_[2][2];                                                                                 \
-        attn_exp(c0, c1, c, m_run * c, l_run, pb_);                                                       \
-        if (MODE != LAST) attn_qk<D>(smem, FP_KBUF(t_ + 1) + k_frag, qb, n0, n1);                         \
+        attn_exp<KT>(c0, c1, c, m_run * c, l_run, pb_);                                                   \
+        if (MODE != LAST) attn_qk<D, KT>(smem, FP_KBUF(t_ + 1) + k_frag, qb, n0, n1);                     \
         {                                                                                                 \
             uint32_t va_[NDT];                                                                            \
             _Pragma("unroll") for (int dt_ = 0; dt_ < NDT; ++dt_) va_[dt_] = FP_VBUF(t_) + v_frag[dt_];   \
-            attn_pv<D>(smem, va_, pb_, acc);                                                              \
+            attn_pv<D, KT>(smem, va_, pb_, acc);                                                          \
         }                                                                                                 \
         if (MODE != LAST) {                                                                               \
-            if (MODE != MAIN) attn_mask(n0, n1, FP_LIM(t_ + 1));                                          \
-            attn_new_max<NDT>(attn_rowmax(n0, n1), c, m_run, l_run, acc);                                 \
+            if (MODE != MAIN) attn_mask<KT>(n0, n1, FP_LIM(t_ + 1));                                      \
+            attn_new_max<NDT>(attn_rowmax<KT>(n0, n1), c, m_run, l_run, acc);                             \
             if (MODE == PEN) FP_WAIT_VMCNT(0);                                                            \
             else FP_WAIT_VMCNT(LPT);                                                                      \
             __syncthreads();                                                                              \
@@ -409,7 +421,7 @@ __global__ __launch_bounds__(256, D > 128 ? 1 : 2) void attn_kernel(
     // and a row only meets it as its diagonal); the list is ascending, so only its last block can
     // be the diagonal one.  A MAIN step t needs tiles t .. t+3 before it.  ntiles is even, and so
     // is the number of MAIN steps, so the register roles of the two S^T tiles alternate evenly.
-    const int n_plain = FP_TILE_BLOCK(nt_real - 1) == I ? TPB * (nb - 1) : nt_real;
+    const int n_plain = FP_TILE_BLOCK(ntiles - 1) == I ? TPB * (nb - 1) : ntiles;
     const int t_main = (n_plain - 3) & ~1;   // negative: none
     int t = 0;
     for (; t < t_main; t += 2) {
