@@ -399,6 +399,9 @@ def main():
     ap.add_argument("--gemm-reference", action="store_true",
                     help="also time a library bf16 GEMM (8192^3), a plain 1 GiB device copy / read, and the own dense "
                          "kernel and the GEMM on all-zero inputs, as context for the MFMA and HBM fractions")
+    ap.add_argument("--data-dependence", action="store_true",
+                    help="only the own dense kernel and the library GEMM on N(0,1) and on all-zero inputs (64K tokens, "
+                         "Qwen3 shape); prints its own JSON line")
     ap.add_argument("--chunk", type=int, default=0,
                     help="chunked prefill: time the path for the last CHUNK tokens of every sequence as queries against "
                          "the whole sequence's keys (multiple of 128); prints its own JSON line")
@@ -432,6 +435,10 @@ def main():
     torch.cuda.set_device(0)
 
     import dataclasses
+    if a.data_dependence:
+        print(json.dumps({"data_dependence_64k": data_dependence(torch, B),
+                          "order": "N(0,1): 9 dense launches, 31 GEMMs; then all zeros: 9 dense launches, 31 GEMMs"}), flush=True)
+        return
     if a.block != 128 and not a.sweep:
         raise SystemExit("--block other than 128 is measured with --sweep (the configurations are stated at block 128)")
     if a.sweep:
