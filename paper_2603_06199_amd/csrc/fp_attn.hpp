@@ -298,39 +298,44 @@ __global__ __launch_bounds__(64 * kAttnWaves<BLK>, D > 128 ? 1 : 2) void attn_ke
         ld_kcol[i] = (uint32_t)((ld_pos ^ (row & kSwz<D>)) * 16);
         ld_vcol[i] = (uint32_t)((ld_pos ^ (4 * (row & kAttnVSwz<D>))) * 16);
     }
-#define FP_LOAD(FULL, Xb, col_, blk_, odd_, ldsoff_)                                                      \
+    // Clamped load of sub-tile sub_ of block blk_: every row is kept at or before the sequence's last token.
+#define FP_LOAD(Xb, col_, blk_, sub_, ldsoff_)                                                            \
     do {                                                                                                  \
-        const int tok0_ = seq_tok0 + (blk_) * BLK + (odd_) * KT;                                          \
+        const int tok0_ = seq_tok0 + (blk_) * BLK + (sub_) * KT;                                          \
         const int base_tok_ = tok0_ < last_tok ? tok0_ : last_tok;                                        \
         const char *base_ = Xb + (size_t)base_tok_ * row_bytes;                                           \
         const uint32_t dst_ = lds_base + (ldsoff_) + 16 * w * RB;                                         \
         _Pragma("unroll") for (int i_ = 0; i_ < LPT; ++i_) {                                              \
-            uint32_t ro_ = (uint32_t)(ld_row + RPL * i_) * row_bytes;                                     \
-            if (!(FULL)) {                                                                                \
-                int tok_ = tok0_ + ld_row + RPL * i_;                                                     \
-                tok_ = tok_ < last_tok ? tok_ : last_tok; /* keys past the end are masked as future */    \
-                ro_ = (uint32_t)(tok_ - base_tok_) * row_bytes; /* tok_ >= base_tok_ */                   \
-            }                                                                                             \
+            int tok_ = tok0_ + ld_row + RPL * i_;                                                         \
+            tok_ = tok_ < last_tok ? tok_ : last_tok; /* keys past the end are masked as future */        \
+            const uint32_t ro_ = (uint32_t)(tok_ - base_tok_) * row_bytes; /* tok_ >= base_tok_ */        \
             load_to_lds(base_, ro_ + col_[i_], dst_ + i_ * 1024);                                         \
         }                                                                                                 \
     } while (0)
     // K tile t lives in K buffer t % 3, V tile t in V buffer t % 2.
 #define FP_KBUF(t) ((uint32_t)(((t) % kAttnKBufs) * kAttnTile<D, KT>))
-#define FP_VBUF(t) ((uint32_t)(kAttnVBase<D, KT> + ((t) & 1) * kAttnTile<D, KT>))
-    // FULL loads are for tiles known to lie before the diagonal block, hence complete; the block id
-    // is kept below I so that even a malformed (non-ascending) list cannot reach past the sequence.
-    // Other loads clamp every row to the sequence's last token, and the tile index to the row's
-    // last tile: a prefetch past the end of the list re-reads that tile into a buffer nobody reads.
-#define FP_LOAD_FULL(Xb, col_, t, ldsoff_)                                                                \
-    do {                                                                                                  \
-        const int b_ = FP_TILE_BLOCK(t);                                                                  \
-        FP_LOAD(true, Xb, col_, (b_ < I ? b_ : I - 1), ((t) % TPB), ldsoff_);                             \
-    } while (0)
+#define FP_VBUF(par) ((uint32_t)(kAttnVBase<D, KT> + (par) * kAttnTile<D, KT>))
+    // Outside the main loop the tile index is kept at the row's last tile: a prefetch past the end
+    // of the list re-reads that tile into a buffer nobody reads.
 #define FP_LOAD_SAFE(Xb, col_, t, ldsoff_)                                                                \
     do {                                                                                                  \
         const int ts_ = (t) < ntiles ? (t) : ntiles - 1;                                                  \
-        FP_LOAD(false, Xb, col_, FP_TILE_BLOCK(ts_), (ts_ % TPB), ldsoff_);                               \
+        FP_LOAD(Xb, col_, FP_TILE_BLOCK(ts_), (ts_ % TPB), ldsoff_);                                      \
     } while (0)
+    // The plain steps of the main loop load tiles known to lie before the diagonal block, hence
+    // complete: no per-row clamp, and the address is a byte offset carried from step to step (see
+    // the loop): off_ = offset of the tile's first row from the KV head's base.
+#define FP_LOAD_AT(Xb, col_, off_, ldsoff_)                                                               \
+    do {                                                                                                  \
+        const char *base_ = Xb + (off_);                                                                  \
+        const uint32_t dst_ = lds_base + (ldsoff_) + 16 * w * RB;                                         \
+        _Pragma("unroll") for (int i_ = 0; i_ < LPT; ++i_)                                                \
+            load_to_lds(base_, (uint32_t)(ld_row + RPL * i_) * row_bytes + col_[i_], dst_ + i_ * 1024);   \
+    } while (0)
+    // Offset of tile u given its list entry; the block id is kept below I so that even a malformed
+    // (non-ascending) list cannot make a plain load reach past the sequence.
+#define FP_ENT_OFF(ent_, u)                                                                               \
+    ((uint64_t)(uint32_t)(seq_tok0 + ((ent_) < 0 ? 0 : ((ent_) < I ? (ent_) : I - 1)) * BLK + ((u) % TPB) * KT) * row_bytes)
 
     f32x16 acc[NDT];
 #pragma unroll
@@ -360,11 +365,11 @@ __global__ __launch_bounds__(64 * kAttnWaves<BLK>, D > 128 ? 1 : 2) void attn_ke
 #define FP_LIM(t) (FP_TILE_BLOCK(t) == I ? qoff + q_local - ((t) % TPB) * KT - 4 * half : 2 * KT)
 
     // Prologue: S^T of tile 0 with its row max; on leaving it K[1] and V[0] are in, K[2] on its way.
-    FP_LOAD(false, Kb, ld_kcol, b0, 0, FP_KBUF(0));
-    FP_LOAD(false, Vb, ld_vcol, b0, 0, FP_VBUF(0));
-    FP_LOAD(false, Kb, ld_kcol, b0, 1, FP_KBUF(1));   // ntiles >= 2
-    if (TPB == 2) FP_LOAD(false, Kb, ld_kcol, (nb > 1 ? b1 : b0), (nb > 1 ? 0 : 1), FP_KBUF(2));
-    else FP_LOAD(false, Kb, ld_kcol, b0, 2, FP_KBUF(2));
+    FP_LOAD(Kb, ld_kcol, b0, 0, FP_KBUF(0));
+    FP_LOAD(Vb, ld_vcol, b0, 0, FP_VBUF(0));
+    FP_LOAD(Kb, ld_kcol, b0, 1, FP_KBUF(1));   // ntiles >= 2
+    if (TPB == 2) FP_LOAD(Kb, ld_kcol, (nb > 1 ? b1 : b0), (nb > 1 ? 0 : 1), FP_KBUF(2));
+    else FP_LOAD(Kb, ld_kcol, b0, 2, FP_KBUF(2));
     FP_WAIT_VMCNT(3 * LPT);   // Q and K[0] are in; V[0], K[1] and K[2] keep landing under the first QK^T
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) asm volatile("" : "+v"(qb[ks]));   // uses of Q stay behind the wait
@@ -387,25 +392,28 @@ __global__ __launch_bounds__(64 * kAttnWaves<BLK>, D > 128 ? 1 : 2) void attn_ke
     //   TAIL  row-clamped loads and the (branch-free) causal limit of tile t+1;
     //   PEN   the last but one step: as TAIL without a K prefetch, ends with nothing in flight;
     //   LAST  exponentials and PV of the last tile only.
+    // PAR is the parity of t (steps come in pairs that start at an even t): V tile t sits in V
+    // buffer PAR.  KB_NEXT / KB_LOAD are the K buffers of tile t+1 (read) and t+3 (loaded); VOFF /
+    // KOFF the byte offsets of tiles t+1 / t+3 (MAIN only).
     // A tile of the diagonal block that lies wholly in a wave's future needs no special case: its
     // logits are all -inf, which leaves the max alone and contributes zeros.
     enum { MAIN = 0, TAIL = 1, PEN = 2, LAST = 3 };
-#define FP_STEP(MODE, t, c0, c1, n0, n1)                                                                  \
+#define FP_STEP(MODE, PAR, t, c0, c1, n0, n1, VOFF, KOFF, KB_NEXT, KB_LOAD)                                \
     do {                                                                                                  \
         const int t_ = (t);                                                                               \
         if (MODE == MAIN) {                                                                               \
-            FP_LOAD_FULL(Vb, ld_vcol, t_ + 1, FP_VBUF(t_ + 1));                                           \
-            FP_LOAD_FULL(Kb, ld_kcol, t_ + 3, FP_KBUF(t_ + 3));                                           \
+            FP_LOAD_AT(Vb, ld_vcol, VOFF, FP_VBUF(1 - PAR));                                              \
+            FP_LOAD_AT(Kb, ld_kcol, KOFF, KB_LOAD);                                                       \
         } else if (MODE != LAST) {                                                                        \
-            FP_LOAD_SAFE(Vb, ld_vcol, t_ + 1, FP_VBUF(t_ + 1));                                           \
-            if (MODE == TAIL) FP_LOAD_SAFE(Kb, ld_kcol, t_ + 3, FP_KBUF(t_ + 3));                         \
+            FP_LOAD_SAFE(Vb, ld_vcol, t_ + 1, FP_VBUF(1 - PAR));                                          \
+            if (MODE == TAIL) FP_LOAD_SAFE(Kb, ld_kcol, t_ + 3, KB_LOAD);                                 \
         }                                                                                                 \
         bf16x8 pb_[2][2];                                                                                 \
         attn_exp<KT>(c0, c1, c, m_run * c, l_run, pb_);                                                   \
-        if (MODE != LAST) attn_qk<D, KT>(smem, FP_KBUF(t_ + 1) + k_frag, qb, n0, n1);                     \
+        if (MODE != LAST) attn_qk<D, KT>(smem, (KB_NEXT) + k_frag, qb, n0, n1);                           \
         {                                                                                                 \
             uint32_t va_[NDT];                                                                            \
-            _Pragma("unroll") for (int dt_ = 0; dt_ < NDT; ++dt_) va_[dt_] = FP_VBUF(t_) + v_frag[dt_];   \
+            _Pragma("unroll") for (int dt_ = 0; dt_ < NDT; ++dt_) va_[dt_] = FP_VBUF(PAR) + v_frag[dt_];  \
             attn_pv<D, KT>(smem, va_, pb_, acc);                                                          \
         }                                                                                                 \
         if (MODE != LAST) {                                                                               \
@@ -424,16 +432,39 @@ __global__ __launch_bounds__(64 * kAttnWaves<BLK>, D > 128 ? 1 : 2) void attn_ke
     const int n_plain = FP_TILE_BLOCK(ntiles - 1) == I ? TPB * (nb - 1) : ntiles;
     const int t_main = (n_plain - 3) & ~1;   // negative: none
     int t = 0;
-    for (; t < t_main; t += 2) {
-        FP_STEP(MAIN, t, sA0, sA1, sB0, sB1);
-        FP_STEP(MAIN, t + 1, sB0, sB1, sA0, sA1);
+    if (t_main > 0) {
+        // Addresses of the main loop, carried instead of recomputed: o1..o3 = offsets of tiles t+1..t+3,
+        // e4 = list entry of tile t+4, fetched one pair of steps before it is needed (a list read is a
+        // scalar memory load; waiting for it inside a step would stall the wave at the step's start);
+        // kb0..kb2 = K buffers of tiles t..t+2.  Tile t+5 is the odd neighbour of t+4 in one block.
+        // (Tiles 0..4 lie in the first 4 / TPB + 1 list entries; the first two are already here.)
+#define FP_ENT(u) ((u) / TPB == 0 ? b0 : ((u) / TPB == 1 ? b1 : (SPARSE ? list[(u) / TPB < nb ? (u) / TPB : nb - 1] : (u) / TPB)))
+        uint64_t o1 = FP_ENT_OFF(FP_ENT(1), 1), o2 = FP_ENT_OFF(FP_ENT(2), 2), o3 = FP_ENT_OFF(FP_ENT(3), 3);
+        int e4 = FP_ENT(4);
+        uint32_t kb0 = FP_KBUF(0), kb1 = FP_KBUF(1), kb2 = FP_KBUF(2);
+        for (; t < t_main; t += 2) {
+            const int u6 = (t + 6) / TPB < nb ? (t + 6) / TPB : nb - 1;
+            const int e6 = SPARSE ? list[u6] : u6;
+            FP_STEP(MAIN, 0, t, sA0, sA1, sB0, sB1, o1, o3, kb1, kb0);
+            const uint64_t o4 = FP_ENT_OFF(e4, t + 4);
+            FP_STEP(MAIN, 1, t + 1, sB0, sB1, sA0, sA1, o2, o4, kb2, kb1);
+            o1 = o3;
+            o2 = o4;
+            o3 = o4 + (uint64_t)KT * row_bytes;
+            e4 = e6;
+            const uint32_t kb_ = kb0;
+            kb0 = kb2;
+            kb2 = kb1;
+            kb1 = kb_;
+        }
+#undef FP_ENT
     }
     for (; t < ntiles - 2; t += 2) {
-        FP_STEP(TAIL, t, sA0, sA1, sB0, sB1);
-        FP_STEP(TAIL, t + 1, sB0, sB1, sA0, sA1);
+        FP_STEP(TAIL, 0, t, sA0, sA1, sB0, sB1, 0, 0, FP_KBUF(t + 1), FP_KBUF(t + 3));
+        FP_STEP(TAIL, 1, t + 1, sB0, sB1, sA0, sA1, 0, 0, FP_KBUF(t + 2), FP_KBUF(t + 4));
     }
-    FP_STEP(PEN, t, sA0, sA1, sB0, sB1);
-    FP_STEP(LAST, t + 1, sB0, sB1, sA0, sA1);
+    FP_STEP(PEN, 0, t, sA0, sA1, sB0, sB1, 0, 0, FP_KBUF(t + 1), 0);
+    FP_STEP(LAST, 1, t + 1, sB0, sB1, sA0, sA1, 0, 0, 0, 0);
 
     // O = acc / l, lse = m + log2 l (Alg. 3, final normalisation); rows past a ragged end are not stored.
     // Each lane holds 4 consecutive dims of one query per accumulator group, which would make every
@@ -471,8 +502,9 @@ __global__ __launch_bounds__(64 * kAttnWaves<BLK>, D > 128 ? 1 : 2) void attn_ke
         lse[(size_t)h * T + q_tok0 + q_local] = l_tot > 0.f ? m_run * c + __log2f(l_tot) : -INFINITY;
 #undef FP_TILE_BLOCK
 #undef FP_LOAD
-#undef FP_LOAD_FULL
 #undef FP_LOAD_SAFE
+#undef FP_LOAD_AT
+#undef FP_ENT_OFF
 #undef FP_LIM
 #undef FP_KBUF
 #undef FP_VBUF
