@@ -1,7 +1,7 @@
 """GPU parity at block sizes 64 and 256 (head dimension 128): the paper fixes the block at 128, a
 serving integration may not.  Every entry point against the oracle at the same block size, through
-the C ABI: a 64-query block half-fills the workgroup's query tile, a 256-query block takes two
-workgroups per row in the attention kernel and one head per workgroup in the search."""
+the C ABI: a 64-query block gets a two-wave attention workgroup over 32-key tiles, a 256-query block
+takes two workgroups per row in the attention kernel and one head per workgroup in the search."""
 import numpy as np
 import pytest
 
