@@ -332,10 +332,13 @@ __global__ __launch_bounds__(64 * kAttnWaves<BLK>, D > 128 ? 1 : 2) void attn_ke
         _Pragma("unroll") for (int i_ = 0; i_ < LPT; ++i_)                                                \
             load_to_lds(base_, (uint32_t)(ld_row + RPL * i_) * row_bytes + col_[i_], dst_ + i_ * 1024);   \
     } while (0)
-    // Offset of tile u given its list entry; the block id is kept below I so that even a malformed
-    // (non-ascending) list cannot make a plain load reach past the sequence.
+    // Offset of tile u given its list entry; the block id is kept inside the blocks that are complete
+    // in memory (those before the diagonal one, and the diagonal one unless the sequence ends inside
+    // it), so that even a malformed (non-ascending) list cannot make a plain load reach past the sequence.
+    const bool diag_full = seq_tok0 + (I + 1) * BLK - 1 <= last_tok;
+    const int ent_max = diag_full ? I : I - 1;
 #define FP_ENT_OFF(ent_, u)                                                                               \
-    ((uint64_t)(uint32_t)(seq_tok0 + ((ent_) < 0 ? 0 : ((ent_) < I ? (ent_) : I - 1)) * BLK + ((u) % TPB) * KT) * row_bytes)
+    ((uint64_t)(uint32_t)(seq_tok0 + ((ent_) < 0 ? 0 : ((ent_) < ent_max ? (ent_) : ent_max)) * BLK + ((u) % TPB) * KT) * row_bytes)
 
     f32x16 acc[NDT];
 #pragma unroll
@@ -388,7 +391,7 @@ __global__ __launch_bounds__(64 * kAttnWaves<BLK>, D > 128 ? 1 : 2) void attn_ke
     // K[t+3].  Every variant is straight-line code, so that the scheduler can interleave the QK^T
     // MFMAs of tile t+1 with the exponentials of tile t, and the PV MFMAs of tile t with the max of
     // tile t+1:
-    //   MAIN  tiles t .. t+3 lie before the diagonal block: cheap loads, no mask;
+    //   MAIN  tile t+1 needs no mask, tiles t+1 and t+3 are complete in memory: cheap loads;
     //   TAIL  row-clamped loads and the (branch-free) causal limit of tile t+1;
     //   PEN   the last but one step: as TAIL without a K prefetch, ends with nothing in flight;
     //   LAST  exponentials and PV of the last tile only.
@@ -427,10 +430,13 @@ __global__ __launch_bounds__(64 * kAttnWaves<BLK>, D > 128 ? 1 : 2) void attn_ke
 
     // Tiles before the diagonal block are complete (only a sequence's last block can be partial,
     // and a row only meets it as its diagonal); the list is ascending, so only its last block can
-    // be the diagonal one.  A MAIN step t needs tiles t .. t+3 before it.  ntiles is even, and so
-    // is the number of MAIN steps, so the register roles of the two S^T tiles alternate evenly.
+    // be the diagonal one: the first n_plain tiles need no mask.  A pair of MAIN steps (t, t+1)
+    // computes S^T of tiles t+1 and t+2 without a mask and loads tiles t+1 .. t+4 without a clamp:
+    // t+2 < n_plain, and t+4 has to exist and be complete, which the diagonal block is unless the
+    // sequence ends inside it (then t+4 < n_plain).  ntiles and n_plain are even, and so is the
+    // number of MAIN steps, so the register roles of the two S^T tiles alternate evenly.
     const int n_plain = FP_TILE_BLOCK(ntiles - 1) == I ? TPB * (nb - 1) : ntiles;
-    const int t_main = (n_plain - 3) & ~1;   // negative: none
+    const int t_main = diag_full ? (n_plain - 2 < ntiles - 4 ? n_plain - 2 : ntiles - 4) : n_plain - 4;   // <= 0: none
     int t = 0;
     if (t_main > 0) {
         // Addresses of the main loop, carried instead of recomputed: o1..o3 = offsets of tiles t+1..t+3,
