@@ -535,14 +535,14 @@ def main():
         "speedup_vs_own_dense": res["speedup_vs_own_dense"], "speedup_vs_own_dense_fused": res["speedup_vs_own_dense_fused"],
         "roofline": {"bound": "mfma", "kernel": "attn_kernel<sparse>", "achieved": res["sparse_tflops"],
                      "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": res["sparse_tflops"] / MFMA_BF16_PEAK_TFLOPS,
-                     "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, f"fp::attn_kernel<{w.head_dim}, true>") or {}).get("bytes"),
-                     "traffic_detail": profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, f"fp::attn_kernel<{w.head_dim}, true>")},
+                     "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, f"fp::attn_kernel<{w.head_dim}, 128, true>") or {}).get("bytes"),
+                     "traffic_detail": profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, f"fp::attn_kernel<{w.head_dim}, 128, true>")},
         "roofline_search": {"bound": "hbm", "kernel": "pool_k_kernel+search_kernel", "achieved": res["search_gbs"],
                             "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": res["search_gbs"] / HBM_PEAK_GBS,
                             "mfma_tflops_two_pass": res["search_mfma_tflops"],
                             "mfma_frac_two_pass": res["search_mfma_tflops"] / MFMA_BF16_PEAK_TFLOPS,
                             "exp2_per_s": res["search_exp2_per_s"],
-                            "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, f"fp::search_kernel<{w.head_dim}, false>") or {}).get("bytes")},
+                            "traffic": (profiled_traffic(w.name.replace("_coherent", "") + "_" + w.mode, f"fp::search_kernel<{w.head_dim}, 128, false>") or {}).get("bytes")},
         "roofline_dense": {"bound": "mfma", "kernel": "attn_kernel<dense>", "achieved": res["dense_tflops"],
                            "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": (res["dense_tflops"] or 0) / MFMA_BF16_PEAK_TFLOPS},
