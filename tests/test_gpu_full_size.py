@@ -141,6 +141,19 @@ def test_qwen3_shape_sampled_rows(cfg, mode):
     _sampled_checks(r, rows_scores, rows_attn, rows_dense)
 
 
+def test_longest_supported_sequence():
+    """4096 key blocks (512K tokens), the most a sequence may have: the search row exactly fills the
+    LDS budget the plan was sized for, the lists have 4096 columns, and the last row's dense pass
+    walks 8192 tiles.  Four query heads on one KV head keep it small; sampled rows against the oracle."""
+    w = synth.small("max_blocks_512k", [4096 * 128], 4, 1, seed=5, n_vert=64, n_slash=4)
+    print(f"\n[full size] {w.name}", flush=True)
+    r = _run(w)
+    n = r["plan"].n_max
+    assert n == 4096 and r["plan"].m_total == 4096
+    _list_properties(r)
+    _sampled_checks(r, sorted({0, 1, 127, 128, 129, n // 2, n - 2, n - 1}), [0, n // 2, n - 1], [n - 1])
+
+
 def test_headline_last_row_every_head_dense_and_listed():
     """Configuration 3 as bench.py runs it (256K tokens, generator as configured): the last q-block
     row sees all 2048 key blocks, the longest row the kernels ever walk.  Every head of it is
