@@ -95,12 +95,18 @@ __device__ __forceinline__ float max3(float a, float b, float c) { return fmaxf(
 // vmcnt nor orders LDS reads after them (it would wait for *all* outstanding loads before the
 // first LDS read of every step, which defeats the prefetch).  Completion is waited for
 // explicitly with FP_WAIT_VMCNT followed by a workgroup barrier.
+// M0 is named as clobbered so that the compiler does not keep a value of its own in it across
+// the statement; it answers with a warning that it will not save and restore a reserved register
+// for us, which is what is wanted here (no code in these kernels needs M0 otherwise).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void load_to_lds(const char *sbase, uint32_t voff, uint32_t lds_addr) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
                  :
                  : "v"(voff), "s"(sbase), "s"(lds_addr)
                  : "memory", "m0");
 }
+#pragma clang diagnostic pop
 
 // s_waitcnt vmcnt(n) alone (expcnt and lgkmcnt left at "no wait"), n < 64: the count's low four
 // bits sit in bits 3:0 of the immediate, its high two in bits 15:14
