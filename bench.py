@@ -399,6 +399,9 @@ def main():
     ap.add_argument("--gemm-reference", action="store_true",
                     help="also time a library bf16 GEMM (8192^3), a plain 1 GiB device copy / read, and the own dense "
                          "kernel and the GEMM on all-zero inputs, as context for the MFMA and HBM fractions")
+    ap.add_argument("--mfma-probe", action="store_true",
+                    help="only run the stand-alone probe of the bare bf16 MFMA rate (operands in registers / from LDS, "
+                         "random / zero operand bits) and print its JSON line")
     ap.add_argument("--data-dependence", action="store_true",
                     help="only the own dense kernel and the library GEMM on N(0,1) and on all-zero inputs (64K tokens, "
                          "Qwen3 shape); prints its own JSON line")
@@ -422,6 +425,13 @@ def main():
     if a.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
         sys.exit(2)
+
+    if a.mfma_probe:      # a child process of its own, started before this one touches the GPU
+        import subprocess
+        from paper_2603_06199_amd import build
+        if not os.path.exists(build.PROBE):
+            build.build()
+        sys.exit(subprocess.run([build.PROBE]).returncode)
 
     import torch
     from paper_2603_06199_amd import binding as B

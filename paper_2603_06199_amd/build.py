@@ -8,6 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflashprefill.so")
+PROBE = os.path.join(HERE, "mfma_probe")     # stand-alone measurement aid (bench.py --mfma-probe), not part of the library
 SOURCES = ["flashprefill.hip"]
 HEADERS = ["fp_device.hpp", "fp_search.hpp", "fp_attn.hpp"]
 
@@ -59,6 +60,10 @@ def build(force: bool = True, verbose: bool = False) -> str:
         if verbose:
             print(" ".join(cmd), flush=True)
         subprocess.run(cmd, check=True)
+        probe = [hipcc] + [f for f in HIPCC_FLAGS if f not in ("-fPIC", "-shared")] + ["-o", PROBE, os.path.join(CSRC, "mfma_probe.hip")]
+        if verbose:
+            print(" ".join(probe), flush=True)
+        subprocess.run(probe, check=True)
     return LIB
 
 
