@@ -16,21 +16,22 @@ pytestmark = pytest.mark.gpu
 torch = pytest.importorskip("torch")
 
 
-def _run(w):
+def _run(w, block=128):
     Q, K, V = synth.make_qkv(w, threads=16)
     cu = w.cu_seqlens
-    plan = B.Plan(cu, w.hq, w.hkv)
+    plan = B.Plan(cu, w.hq, w.hkv, block=block)
     dQ, dK, dV = dev(Q), dev(K), dev(V)
     P = plan.fp_block_search(dQ, dK)
     idx, cnt = plan.fp_threshold(P, w.alpha)
     O, lse = plan.fp_sparse_prefill(dQ, dK, dV, idx, cnt)
     torch.cuda.synchronize()
-    return dict(w=w, cu=cu, Q=Q, K=K, V=V, plan=plan, dQ=dQ, dK=dK, dV=dV, P=P, idx=idx, cnt=cnt, O=O, lse=lse)
+    return dict(w=w, cu=cu, Q=Q, K=K, V=V, plan=plan, dQ=dQ, dK=dK, dV=dV, P=P, idx=idx, cnt=cnt, O=O, lse=lse, block=block)
 
 
 def _list_properties(r):
     """Causal, in range, ascending, duplicate-free, sink and window blocks present: on every row."""
     plan, idx, cnt = r["plan"], r["idx"], r["cnt"]
+    sinkB, winB = -(-256 // r["block"]), -(-512 // r["block"])       # always-kept blocks: sink 256 and window 512 tokens
     hq, m, n = idx.shape
     ro = plan.row_offset
     I = torch.cat([torch.arange(ro[s + 1] - ro[s]) for s in range(len(ro) - 1)]).cuda()          # block index of each row
@@ -40,9 +41,9 @@ def _list_properties(r):
     assert bool(((idx >= 0) & (idx <= I[None, :, None]))[valid].all())
     asc = (idx[:, :, 1:] > idx[:, :, :-1]) | ~valid[:, :, 1:]
     assert bool(asc.all())
-    # always-kept blocks: J < 2 and I-3..I  ->  count of listed J with J < 2 or I - J < 4 equals the structural count
-    structural = ((idx < 2) | ((I[None, :, None] - idx) < 4)) & valid
-    want = torch.where(I <= 5, I + 1, torch.tensor(6, device="cuda"))      # |{0,1} u {I-3..I}| = min(I+1, 6)
+    # J < sinkB and I-winB+1..I  ->  count of listed J with J < sinkB or I - J < winB equals the structural count
+    structural = ((idx < sinkB) | ((I[None, :, None] - idx) < winB)) & valid
+    want = torch.where(I < sinkB + winB, I + 1, torch.tensor(sinkB + winB, device="cuda"))   # |{0..sinkB-1} u {I-winB+1..I}|
     assert bool((structural.sum(dim=2) == want[None, :]).all())
 
 
@@ -67,24 +68,24 @@ def _lists_same_outside_band(idx_a, cnt_a, idx_b, cnt_b, P, alpha):
 
 
 def _sampled_checks(r, rows_scores, rows_attn, rows_dense):
-    w, cu = r["w"], r["cu"]
-    P_ref = oracle.block_search(r["Q"], r["K"], cu, rows=rows_scores)
+    w, cu, blk = r["w"], r["cu"], r["block"]
+    P_ref = oracle.block_search(r["Q"], r["K"], cu, block=blk, rows=rows_scores)
     P_gpu = r["P"].cpu().numpy()
-    compare_scores(P_gpu, P_ref, cu, rows=rows_scores)
-    nd, nb = compare_lists_banded(r["idx"].cpu().numpy(), r["cnt"].cpu().numpy(), P_ref, cu, w.alpha, rows=rows_scores)
+    compare_scores(P_gpu, P_ref, cu, rows=rows_scores, block=blk)
+    nd, nb = compare_lists_banded(r["idx"].cpu().numpy(), r["cnt"].cpu().numpy(), P_ref, cu, w.alpha, rows=rows_scores, block=blk)
     print(f"{w.name}: {len(rows_scores)} sampled rows: list mismatches {nd}, pairs in the near-threshold band {nb}")
     # the one-pass entry point: same band rule against the oracle on the sampled rows, and on every
     # row the same lists as the two calls above
     idx_f, cnt_f = r["plan"].fp_search_select(r["dQ"], r["dK"], w.alpha)
     torch.cuda.synchronize()
-    compare_lists_banded(idx_f.cpu().numpy(), cnt_f.cpu().numpy(), P_ref, cu, w.alpha, rows=rows_scores)
+    compare_lists_banded(idx_f.cpu().numpy(), cnt_f.cpu().numpy(), P_ref, cu, w.alpha, rows=rows_scores, block=blk)
     nd = _lists_same_outside_band(idx_f, cnt_f, r["idx"], r["cnt"], r["P"], w.alpha)
     print(f"{w.name}: one-pass vs two-call lists over all rows: {nd} differing pairs, all inside the near-threshold band")
     del idx_f, cnt_f
     # sparse attention on the GPU's own lists vs the oracle given the same lists
     idx_h, cnt_h = r["idx"].cpu().numpy(), r["cnt"].cpu().numpy()
-    O_ref, lse_ref = oracle.sparse_prefill(r["Q"], r["K"], r["V"], cu, idx_h, cnt_h, rows=rows_attn)
-    toks = row_tokens(cu, rows_attn)
+    O_ref, lse_ref = oracle.sparse_prefill(r["Q"], r["K"], r["V"], cu, idx_h, cnt_h, block=blk, rows=rows_attn)
+    toks = row_tokens(cu, rows_attn, block=blk)
     tt = torch.from_numpy(toks).cuda()
     mx, mean = compare_O(r["O"][tt].float().cpu().numpy(), O_ref[toks])
     np.testing.assert_allclose(r["lse"][:, tt].cpu().numpy(), lse_ref[:, toks], atol=LSE_ATOL, rtol=0)
@@ -92,8 +93,8 @@ def _sampled_checks(r, rows_scores, rows_attn, rows_dense):
     if rows_dense:
         Od, lsed = r["plan"].fp_dense_prefill(r["dQ"], r["dK"], r["dV"])
         torch.cuda.synchronize()
-        Od_ref, lsed_ref = oracle.dense_prefill(r["Q"], r["K"], r["V"], cu, rows=rows_dense)
-        toks = row_tokens(cu, rows_dense)
+        Od_ref, lsed_ref = oracle.dense_prefill(r["Q"], r["K"], r["V"], cu, block=blk, rows=rows_dense)
+        toks = row_tokens(cu, rows_dense, block=blk)
         tt = torch.from_numpy(toks).cuda()
         mx, mean = compare_O(Od[tt].float().cpu().numpy(), Od_ref[toks])
         np.testing.assert_allclose(lsed[:, tt].cpu().numpy(), lsed_ref[:, toks], atol=LSE_ATOL, rtol=0)
@@ -152,6 +153,19 @@ def test_longest_supported_sequence():
     assert n == 4096 and r["plan"].m_total == 4096
     _list_properties(r)
     _sampled_checks(r, sorted({0, 1, 127, 128, 129, n // 2, n - 2, n - 1}), [0, n // 2, n - 1], [n - 1])
+
+
+@pytest.mark.parametrize("blk,tokens", [(64, 131072), (256, 262144)])
+def test_other_block_sizes_at_long_lengths(blk, tokens):
+    """Blocks of 64 and 256 tokens on sequences of 2048 and 1024 blocks (8 query heads on 2 KV heads):
+    sampled rows against the oracle at the same block size."""
+    w = synth.small(f"block{blk}_{tokens // 1024}k", [tokens], 8, 2, seed=9, n_vert=64, n_slash=4)
+    print(f"\n[full size] {w.name}", flush=True)
+    r = _run(w, block=blk)
+    n = r["plan"].n_max
+    assert n == tokens // blk
+    _list_properties(r)
+    _sampled_checks(r, sorted({0, 1, 5, n // 3, n - 2, n - 1}), [0, n // 2, n - 1], [n // 16])
 
 
 def test_headline_last_row_every_head_dense_and_listed():
